@@ -1,0 +1,125 @@
+"""ctypes binding of the C oracle (oracle/varlen_attn_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Argument marshalling only; the arithmetic is in the C file.  Inputs are numpy float32
+arrays holding bf16-representable values (any float32 works), outputs are float64.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "varlen_attn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_attn.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, no fast-math, OpenMP)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        ci, cd = ctypes.c_int, ctypes.c_double
+        lib.oracle_varlen_attn_fwd.argtypes = [f32p, f32p, f32p, i32p, ci, ci, ci, ci, ci, cd, f64p, f64p]
+        lib.oracle_varlen_attn_fwd.restype = ci
+        lib.oracle_varlen_attn_fwd_rows.argtypes = [f32p, f32p, f32p, i32p, ci, ci, ci, ci, ci, cd,
+                                                    i64p, ctypes.c_int64, f64p, f64p]
+        lib.oracle_varlen_attn_fwd_rows.restype = ci
+        lib.oracle_varlen_attn_bwd.argtypes = [f32p, f32p, f32p, f32p, i32p, ci, ci, ci, ci, ci, cd,
+                                               f64p, f64p, f64p]
+        lib.oracle_varlen_attn_bwd.restype = ci
+        lib.oracle_num_threads.restype = ci
+        _lib = lib
+    return _lib
+
+
+def _f32(a, shape):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.shape != shape:
+        raise ValueError(f"expected shape {shape}, got {a.shape}")
+    return a
+
+
+def _ptr(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+def _shapes(q, k, cu):
+    cu = np.ascontiguousarray(cu, dtype=np.int32)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if cu.ndim != 1 or cu.size < 1 or int(cu[-1]) != T:
+        raise ValueError("cu_seqlens must be 1-D with cu[-1] == total tokens")
+    return cu, T, Hq, Hkv, D
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def fwd(q, k, v, cu_seqlens, causal, scale):
+    """O [T,Hq,D] float64 and LSE [Hq,T] float64 (natural log) for every packed row."""
+    lib = _load()
+    cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
+    q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
+    o = np.empty((T, Hq, D), np.float64)
+    lse = np.empty((Hq, T), np.float64)
+    rc = lib.oracle_varlen_attn_fwd(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float),
+                                    _ptr(v, ctypes.c_float), _ptr(cu, ctypes.c_int32), cu.size - 1,
+                                    Hq, Hkv, D, int(bool(causal)), float(scale),
+                                    _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc:
+        raise RuntimeError(f"oracle fwd failed with status {rc}")
+    return o, lse
+
+
+def fwd_rows(q, k, v, cu_seqlens, causal, scale, rows):
+    """O [n,Hq,D] and LSE [n,Hq] float64 for the listed packed rows only (exact per row)."""
+    lib = _load()
+    cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
+    q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    o = np.empty((rows.size, Hq, D), np.float64)
+    lse = np.empty((rows.size, Hq), np.float64)
+    rc = lib.oracle_varlen_attn_fwd_rows(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float),
+                                         _ptr(v, ctypes.c_float), _ptr(cu, ctypes.c_int32),
+                                         cu.size - 1, Hq, Hkv, D, int(bool(causal)), float(scale),
+                                         _ptr(rows, ctypes.c_int64), rows.size,
+                                         _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc:
+        raise RuntimeError(f"oracle fwd_rows failed with status {rc}")
+    return o, lse
+
+
+def bwd(q, k, v, dout, cu_seqlens, causal, scale):
+    """dQ [T,Hq,D], dK, dV [T,Hkv,D] float64, from the oracle's own fp64 forward."""
+    lib = _load()
+    cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
+    q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
+    dout = _f32(dout, (T, Hq, D))
+    dq = np.empty((T, Hq, D), np.float64)
+    dk = np.empty((T, Hkv, D), np.float64)
+    dv = np.empty((T, Hkv, D), np.float64)
+    rc = lib.oracle_varlen_attn_bwd(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float),
+                                    _ptr(v, ctypes.c_float), _ptr(dout, ctypes.c_float),
+                                    _ptr(cu, ctypes.c_int32), cu.size - 1, Hq, Hkv, D,
+                                    int(bool(causal)), float(scale), _ptr(dq, ctypes.c_double),
+                                    _ptr(dk, ctypes.c_double), _ptr(dv, ctypes.c_double))
+    if rc:
+        raise RuntimeError(f"oracle bwd failed with status {rc}")
+    return dq, dk, dv
