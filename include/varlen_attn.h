@@ -1,0 +1,113 @@
+/*
+ * varlen_attn.h -- C ABI of the MI355X (gfx950) variable-length packed self-attention library.
+ *
+ * The operation.  The paper trains multimodal LLMs on packed sequences: samples of different
+ * lengths are concatenated into one token stream and must not attend to each other (Section
+ * 2.1, hybrid packing, Fig. 3c).  Encoder (ViT) attention is full inside a sample (Section 2.2;
+ * Section 4.1.1: the Ulysses state keeps full attention per rank), LLM attention is causal
+ * (Section 4.1.1, parallelism selection rationale), and the attention layers use an exact tiled
+ * algorithm (Section 5, "Efficient Operators").  The paper prints no formula; the library
+ * computes the textbook one.  For sample s with rows [cu[s], cu[s+1]), query head h and kv head
+ * c = h / (Hq / Hkv):
+ *
+ *     S_ij  = softmax_scale * <Q[i,h,:], K[j,c,:]>,   j in the same sample, and j <= i if causal
+ *     LSE_i = ln sum_j exp(S_ij)                       (natural log, scale inside)
+ *     O[i,h,:] = sum_j exp(S_ij - LSE_i) * V[j,c,:]
+ *
+ * and the gradients of sum(O * dO) with respect to Q, K and V.  Inputs and O/dQ/dK/dV are bf16,
+ * products accumulate in fp32 on the matrix cores, LSE is fp32.
+ *
+ * Pointers.  Every tensor pointer is a DEVICE pointer owned by the caller and must be 16-byte
+ * aligned; `p` is a HOST pointer.  The library never allocates, frees or synchronises: all work
+ * is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default stream), and the
+ * buffers must stay alive until the stream has run it.  Outputs are fully overwritten.  The
+ * workspace is scratch; its contents mean nothing between calls, and two calls that share one
+ * workspace must be ordered on one stream.
+ *
+ * Layouts (row-major, contiguous):
+ *     q, o, dout, dq : bf16 [total_tokens, num_q_heads,  head_dim]
+ *     k, v, dk, dv   : bf16 [total_tokens, num_kv_heads, head_dim]
+ *     lse            : fp32 [num_q_heads, total_tokens]
+ *     cu_seqlens     : int32 [num_seqs + 1], cu[0] = 0, non-decreasing, cu[num_seqs] = total_tokens
+ * Empty samples (cu[s] == cu[s+1]) are legal.  The contents of cu_seqlens live on the device and
+ * are NOT validated; violating the precondition above is undefined behaviour.
+ *
+ * Errors.  Every argument the host can see is validated before anything is launched; on error
+ * nothing has been enqueued.  total_tokens == 0 or num_seqs == 0 returns VA_OK with no launch.
+ */
+#ifndef VARLEN_ATTN_H
+#define VARLEN_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    VA_OK = 0,
+    VA_ERR_NULL_PTR = 1,            /* a required pointer is NULL */
+    VA_ERR_BAD_SHAPE = 2,           /* negative size, heads < 1, Hq % Hkv != 0, causal not 0/1 */
+    VA_ERR_UNSUPPORTED = 3,         /* head_dim not in {64, 80, 96, 128}, or device is not gfx950 */
+    VA_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below the *_workspace_bytes() answer */
+    VA_ERR_BAD_SCALE = 5,           /* softmax_scale is NaN, infinite or negative */
+    VA_ERR_HIP = 6,                 /* a HIP call failed; see varlen_attn_last_hip_error() */
+    VA_ERR_MISALIGNED = 7           /* a tensor or workspace pointer is not 16-byte aligned */
+};
+
+typedef struct {
+    int32_t total_tokens;  /* T   >= 0 */
+    int32_t num_seqs;      /* B   >= 0 */
+    int32_t num_q_heads;   /* Hq  >= 1 */
+    int32_t num_kv_heads;  /* Hkv >= 1, Hq % Hkv == 0; q head h reads kv head h / (Hq/Hkv) */
+    int32_t head_dim;      /* D in {64, 80, 96, 128} */
+    int32_t causal;        /* 0: full attention inside a sample; 1: j <= i inside a sample */
+    float softmax_scale;   /* finite, >= 0 (0 is legal: uniform attention) */
+    int32_t reserved;      /* must be 0 */
+} varlen_attn_params;
+
+/* Bytes of device scratch the forward / backward call needs for these sizes (0 on bad params). */
+size_t varlen_attn_fwd_workspace_bytes(const varlen_attn_params *p);
+size_t varlen_attn_bwd_workspace_bytes(const varlen_attn_params *p);
+
+/*
+ * Forward: writes o and lse.  Steps (all on the device): a length-aware scheduler turns
+ * cu_seqlens into a list of 128-row query tiles ordered by decreasing cost; one workgroup per
+ * (tile, head) streams the sample's K/V through LDS, S = QK^T and PV on bf16 MFMA, online softmax.
+ */
+int varlen_attn_fwd(const varlen_attn_params *p,
+                    const void *q, const void *k, const void *v,
+                    const int32_t *cu_seqlens,
+                    void *o, float *lse,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward: writes dq, dk, dv from dout and the forward's saved o and lse (P is recomputed from
+ * q, k and lse, as the paper's recomputation of core attention implies, Section 5 "Selective
+ * Activation Offloading").  dk and dv are summed over the query heads that share a kv head.
+ */
+int varlen_attn_bwd(const varlen_attn_params *p,
+                    const void *dout, const void *q, const void *k, const void *v,
+                    const void *o, const float *lse,
+                    const int32_t *cu_seqlens,
+                    void *dq, void *dk, void *dv,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *varlen_attn_status_string(int status);
+
+/* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int varlen_attn_last_hip_error(void);
+
+/*
+ * Number of scheduler work items the forward (which = 0), the backward dK/dV pass (1) or the
+ * backward dQ pass (2) launches at most for these sizes: the grid is this times the head count
+ * of that pass.  Host arithmetic only; for tests and benchmarks.
+ */
+int64_t varlen_attn_max_work_items(const varlen_attn_params *p, int which);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARLEN_ATTN_H */

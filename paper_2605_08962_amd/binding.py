@@ -1,0 +1,149 @@
+"""Python binding of libvarlen_attn.so: argument marshalling only.
+
+Every step of the attention path runs in the library's HIP kernels.  PyTorch is used for device
+memory (outputs, workspace) and for the current stream handle, nothing else.  There is no CPU or
+eager fallback: if the library is missing or a call fails, this raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
+_lib = None
+
+VA_OK = 0
+
+
+class VarlenAttnError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"varlen_attn status {status}: {message}")
+        self.status = status
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("total_tokens", ctypes.c_int32), ("num_seqs", ctypes.c_int32),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32)]
+
+
+def load():
+    """Load the C-ABI library (building it first only when no built library is present)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    pp = ctypes.POINTER(Params)
+    lib.varlen_attn_fwd_workspace_bytes.argtypes = [pp]
+    lib.varlen_attn_fwd_workspace_bytes.restype = sz
+    lib.varlen_attn_bwd_workspace_bytes.argtypes = [pp]
+    lib.varlen_attn_bwd_workspace_bytes.restype = sz
+    lib.varlen_attn_max_work_items.argtypes = [pp, ctypes.c_int]
+    lib.varlen_attn_max_work_items.restype = ctypes.c_int64
+    lib.varlen_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.varlen_attn_fwd.restype = ctypes.c_int
+    lib.varlen_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.varlen_attn_bwd.restype = ctypes.c_int
+    lib.varlen_attn_status_string.argtypes = [ctypes.c_int]
+    lib.varlen_attn_status_string.restype = ctypes.c_char_p
+    lib.varlen_attn_last_hip_error.argtypes = []
+    lib.varlen_attn_last_hip_error.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load().varlen_attn_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != VA_OK:
+        msg = status_string(status)
+        if status == 6:
+            msg += f" (hipError_t {load().varlen_attn_last_hip_error()})"
+        raise VarlenAttnError(status, msg)
+
+
+def make_params(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, causal, softmax_scale):
+    return Params(int(total_tokens), int(num_seqs), int(num_q_heads), int(num_kv_heads), int(head_dim),
+                  int(bool(causal)), float(softmax_scale), 0)
+
+
+def _params_of(q, k, cu_seqlens, causal, softmax_scale):
+    T, Hq, D = q.shape
+    return make_params(T, cu_seqlens.numel() - 1, Hq, k.shape[1], D, causal, softmax_scale)
+
+
+def _require(t, dtype, name):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+
+
+def fwd_workspace_bytes(params):
+    return int(load().varlen_attn_fwd_workspace_bytes(ctypes.byref(params)))
+
+
+def bwd_workspace_bytes(params):
+    return int(load().varlen_attn_bwd_workspace_bytes(ctypes.byref(params)))
+
+
+def max_work_items(params, which=0):
+    return int(load().varlen_attn_max_work_items(ctypes.byref(params), which))
+
+
+def _stream_handle(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def varlen_attn_fwd(q, k, v, cu_seqlens, causal, softmax_scale, out=None, lse=None, workspace=None,
+                    stream=None):
+    """O bf16 [T,Hq,D] and LSE fp32 [Hq,T] of packed attention; asynchronous on the stream."""
+    lib = load()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _require(t, torch.bfloat16, n)
+    _require(cu_seqlens, torch.int32, "cu_seqlens")
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale)
+    if k.shape != v.shape or k.shape[0] != q.shape[0] or k.shape[2] != q.shape[2]:
+        raise ValueError("k and v must be [T, Hkv, D] matching q's T and D")
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((q.shape[1], q.shape[0]), dtype=torch.float32, device=q.device)
+    need = fwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib.varlen_attn_fwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                               cu_seqlens.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+    return out, lse
+
+
+def varlen_attn_bwd(dout, q, k, v, out, lse, cu_seqlens, causal, softmax_scale, dq=None, dk=None,
+                    dv=None, workspace=None, stream=None):
+    """dQ, dK, dV (bf16) from dO and the forward's saved O and LSE; asynchronous on the stream."""
+    lib = load()
+    for t, n in ((dout, "dout"), (q, "q"), (k, "k"), (v, "v"), (out, "out")):
+        _require(t, torch.bfloat16, n)
+    _require(lse, torch.float32, "lse")
+    _require(cu_seqlens, torch.int32, "cu_seqlens")
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale)
+    if dout.shape != q.shape or out.shape != q.shape or k.shape != v.shape:
+        raise ValueError("dout and out must match q; k must match v")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = bwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib.varlen_attn_bwd(ctypes.byref(p), dout.data_ptr(), q.data_ptr(), k.data_ptr(),
+                               v.data_ptr(), out.data_ptr(), lse.data_ptr(), cu_seqlens.data_ptr(),
+                               dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
+                               workspace.numel(), _stream_handle(stream)))
+    return dq, dk, dv

@@ -1,0 +1,183 @@
+// C-ABI entry points of libvarlen_attn.so: argument validation, workspace carving, launches.
+#include <cmath>
+#include <cstring>
+
+#include "../../include/varlen_attn.h"
+#include "va_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return VA_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_params(const varlen_attn_params* p) {
+    if (!p) return VA_ERR_NULL_PTR;
+    if (p->total_tokens < 0 || p->num_seqs < 0 || p->num_q_heads < 1 || p->num_kv_heads < 1 ||
+        p->num_q_heads % p->num_kv_heads != 0 || (p->causal != 0 && p->causal != 1) || p->reserved != 0)
+        return VA_ERR_BAD_SHAPE;
+    if (p->head_dim != 64 && p->head_dim != 80 && p->head_dim != 96 && p->head_dim != 128)
+        return VA_ERR_UNSUPPORTED;
+    if (!std::isfinite(p->softmax_scale) || p->softmax_scale < 0.f) return VA_ERR_BAD_SCALE;
+    // grid sizes and packed offsets are 32-bit in places: keep the launch within them
+    int64_t items = (int64_t)p->total_tokens / 64 + p->num_seqs;
+    if (items * p->num_q_heads >= (int64_t)1 << 31) return VA_ERR_BAD_SHAPE;
+    return VA_OK;
+}
+
+// The current device must be a gfx950; checked once per device.
+int check_device() {
+    static thread_local int checked_dev = -1;
+    static thread_local int checked_rc = VA_OK;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev == checked_dev) return checked_rc;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return hip_fail(e);
+    checked_dev = dev;
+    checked_rc = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? VA_OK : VA_ERR_UNSUPPORTED;
+    return checked_rc;
+}
+
+struct BwdLayout {
+    va::SchedLayout kv, q;
+    size_t kv_ofs, q_ofs, delta_ofs, end;
+};
+
+BwdLayout bwd_layout(const varlen_attn_params* p) {
+    BwdLayout b;
+    b.kv = va::sched_layout(p->total_tokens, p->num_seqs, va::BWD_TILE_KV);
+    b.q = va::sched_layout(p->total_tokens, p->num_seqs, va::BWD_TILE_Q);
+    b.kv_ofs = 0;
+    b.q_ofs = b.kv.end_ofs;
+    b.delta_ofs = b.q_ofs + b.q.end_ofs;
+    b.end = b.delta_ofs + ((size_t)p->total_tokens * p->num_q_heads * sizeof(float) + 255) / 256 * 256;
+    return b;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t varlen_attn_fwd_workspace_bytes(const varlen_attn_params* p) {
+    if (check_params(p) != VA_OK) return 0;
+    return va::sched_layout(p->total_tokens, p->num_seqs, va::FWD_TILE_Q).end_ofs;
+}
+
+size_t varlen_attn_bwd_workspace_bytes(const varlen_attn_params* p) {
+    if (check_params(p) != VA_OK) return 0;
+    return bwd_layout(p).end;
+}
+
+int64_t varlen_attn_max_work_items(const varlen_attn_params* p, int which) {
+    if (check_params(p) != VA_OK) return 0;
+    int rows = which == 0 ? va::FWD_TILE_Q : which == 1 ? va::BWD_TILE_KV : va::BWD_TILE_Q;
+    return va::sched_layout(p->total_tokens, p->num_seqs, rows).max_items;
+}
+
+int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, const void* v,
+                    const int32_t* cu_seqlens, void* o, float* lse, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != VA_OK) return rc;
+    if (p->total_tokens == 0 || p->num_seqs == 0) return VA_OK;
+    if (!q || !k || !v || !cu_seqlens || !o || !lse || !workspace) return VA_ERR_NULL_PTR;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(workspace) ||
+        ((uintptr_t)lse & 3u) || ((uintptr_t)cu_seqlens & 3u))
+        return VA_ERR_MISALIGNED;
+    va::SchedLayout lay = va::sched_layout(p->total_tokens, p->num_seqs, va::FWD_TILE_Q);
+    if (workspace_bytes < lay.end_ofs) return VA_ERR_WORKSPACE_TOO_SMALL;
+    rc = check_device();
+    if (rc != VA_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    hipError_t e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::FWD_TILE_Q, va::FWD_TILE_KV,
+                                        p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, workspace,
+                                        lay, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    va::FwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.sched_hdr = (const int32_t*)workspace;
+    a.items = (const va::WorkItem*)((const char*)workspace + lay.items_ofs);
+    a.max_items = lay.max_items;
+    a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
+    e = va::launch_fwd(a, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return VA_OK;
+}
+
+int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q, const void* k,
+                    const void* v, const void* o, const float* lse, const int32_t* cu_seqlens,
+                    void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != VA_OK) return rc;
+    if (p->total_tokens == 0 || p->num_seqs == 0) return VA_OK;
+    if (!dout || !q || !k || !v || !o || !lse || !cu_seqlens || !dq || !dk || !dv || !workspace)
+        return VA_ERR_NULL_PTR;
+    if (!aligned16(dout) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) ||
+        ((uintptr_t)lse & 3u) || ((uintptr_t)cu_seqlens & 3u))
+        return VA_ERR_MISALIGNED;
+    BwdLayout lay = bwd_layout(p);
+    if (workspace_bytes < lay.end) return VA_ERR_WORKSPACE_TOO_SMALL;
+    rc = check_device();
+    if (rc != VA_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+
+    hipError_t e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_KV, va::BWD_STEP_Q,
+                                        p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL,
+                                        ws + lay.kv_ofs, lay.kv, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_Q, va::BWD_STEP_KV,
+                             p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q,
+                             stream);
+    if (e != hipSuccess) return hip_fail(e);
+
+    va::BwdArgs a;
+    a.dout = dout; a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.delta = (float*)(ws + lay.delta_ofs);
+    a.dq = dq; a.dk = dk; a.dv = dv;
+    a.sched_hdr_kv = (const int32_t*)(ws + lay.kv_ofs);
+    a.items_kv = (const va::WorkItem*)(ws + lay.kv_ofs + lay.kv.items_ofs);
+    a.max_items_kv = lay.kv.max_items;
+    a.sched_hdr_q = (const int32_t*)(ws + lay.q_ofs);
+    a.items_q = (const va::WorkItem*)(ws + lay.q_ofs + lay.q.items_ofs);
+    a.max_items_q = lay.q.max_items;
+    a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
+    e = va::launch_bwd_delta(a, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = va::launch_bwd_dkdv(a, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = va::launch_bwd_dq(a, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return VA_OK;
+}
+
+const char* varlen_attn_status_string(int status) {
+    switch (status) {
+        case VA_OK: return "ok";
+        case VA_ERR_NULL_PTR: return "a required pointer is NULL";
+        case VA_ERR_BAD_SHAPE: return "bad shape: negative size, head counts, causal flag, reserved field or launch too large";
+        case VA_ERR_UNSUPPORTED: return "unsupported: head_dim must be 64, 80, 96 or 128 and the device gfx950";
+        case VA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case VA_ERR_BAD_SCALE: return "softmax_scale must be finite and >= 0";
+        case VA_ERR_HIP: return "a HIP call failed";
+        case VA_ERR_MISALIGNED: return "a tensor or workspace pointer is not 16-byte aligned";
+        default: return "unknown status";
+    }
+}
+
+int varlen_attn_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

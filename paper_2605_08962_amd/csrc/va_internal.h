@@ -1,0 +1,71 @@
+// Internal host-side declarations shared by the translation units of libvarlen_attn.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace va {
+
+// Scheduler work item: one tile of `rows` consecutive rows of one sample.
+//   x = first packed row of the tile, y = first packed row of the sample,
+//   z = one past the sample's last packed row, w = tile index inside the sample.
+typedef int4 WorkItem;
+
+// How the cost of a tile (the number of partner tiles it loops over) is derived.
+enum CostMode {
+    COST_FULL = 0,          // every tile of a sample meets the whole sample
+    COST_CAUSAL_QUERY = 1,  // query tile t meets keys [0, end of tile t]
+    COST_CAUSAL_KEY = 2     // key tile t meets queries [start of tile t, L)
+};
+
+// Layout of the scheduler's part of a workspace (all int32):
+//   [0] n_items   [1..15] reserved   [16 .. 16+B] tile offsets per sample   then the work items.
+struct SchedLayout {
+    size_t tile_off_ofs;  // bytes
+    size_t items_ofs;     // bytes, 16-byte aligned
+    size_t end_ofs;       // bytes, 256-byte aligned
+    int64_t max_items;
+};
+SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows);
+
+// Enqueue the scheduler: fills header, tile offsets and the cost-sorted work list at `ws`.
+hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_rows, int partner_rows,
+                            CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream);
+
+struct FwdArgs {
+    const void *q, *k, *v;
+    void* o;
+    float* lse;
+    const int32_t* sched_hdr;
+    const WorkItem* items;
+    int64_t max_items;
+    int total_tokens, num_q_heads, num_kv_heads, head_dim, causal;
+    float scale;
+};
+constexpr int FWD_TILE_Q = 128;
+constexpr int FWD_TILE_KV = 64;
+hipError_t launch_fwd(const FwdArgs& a, hipStream_t stream);
+
+struct BwdArgs {
+    const void *dout, *q, *k, *v, *o;
+    const float* lse;
+    float* delta;  // fp32 [Hq, T] scratch
+    void *dq, *dk, *dv;
+    const int32_t* sched_hdr_kv;
+    const WorkItem* items_kv;
+    int64_t max_items_kv;
+    const int32_t* sched_hdr_q;
+    const WorkItem* items_q;
+    int64_t max_items_q;
+    int total_tokens, num_q_heads, num_kv_heads, head_dim, causal;
+    float scale;
+};
+constexpr int BWD_TILE_KV = 128;  // rows of K/V one dK/dV workgroup owns
+constexpr int BWD_STEP_Q = 64;    // query rows it stages per step
+constexpr int BWD_TILE_Q = 128;   // rows of Q one dQ workgroup owns
+constexpr int BWD_STEP_KV = 64;   // key rows it stages per step
+hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_dkdv(const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream);
+
+}  // namespace va

@@ -1,0 +1,135 @@
+// Length-aware tile scheduler.
+//
+// The paper's motivation is the imbalance that mixed long and short samples cause (Section 2.2,
+// Section 4.1.1) and it picks its attention algorithm for its work partitioning on long inputs
+// (Section 5, "Efficient Operators").  On one GPU the same problem shows up inside a single
+// launch: a 64k-token sample packed with hundreds of short ones.  This kernel turns cu_seqlens
+// into a list of row tiles sorted by decreasing cost (the number of partner tiles a tile loops
+// over), entirely on the device.  The compute kernels launch one workgroup per (list entry,
+// head) in list order, so the hardware dispatcher hands out the heaviest tiles first and the
+// light ones fill the tail (longest-processing-time-first list scheduling).
+#include "va_internal.h"
+
+namespace va {
+
+constexpr int SCHED_THREADS = 1024;
+constexpr int SCHED_BINS = 4096;  // costs above SCHED_BINS-1 share the top bin
+
+SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows) {
+    SchedLayout lay;
+    lay.max_items = total_tokens / tile_rows + num_seqs;  // >= sum_s ceil(L_s / tile_rows)
+    lay.tile_off_ofs = 16 * sizeof(int32_t);
+    size_t p = lay.tile_off_ofs + (size_t)(num_seqs + 1) * sizeof(int32_t);
+    lay.items_ofs = (p + 15) / 16 * 16;
+    p = lay.items_ofs + (size_t)lay.max_items * sizeof(WorkItem);
+    lay.end_ofs = (p + 255) / 256 * 256;
+    return lay;
+}
+
+// Exclusive scan of one value per thread over the block; returns the exclusive prefix and
+// writes the block total to *total.  `buf` holds SCHED_THREADS ints.
+__device__ int block_exclusive_scan(int v, int* buf, int* total) {
+    const int t = threadIdx.x;
+    buf[t] = v;
+    __syncthreads();
+    for (int d = 1; d < SCHED_THREADS; d <<= 1) {
+        int add = (t >= d) ? buf[t - d] : 0;
+        __syncthreads();
+        buf[t] += add;
+        __syncthreads();
+    }
+    int incl = buf[t];
+    *total = buf[SCHED_THREADS - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__device__ __forceinline__ int tile_cost(int L, int t, int R, int U, int mode) {
+    int span;
+    if (mode == COST_FULL) span = L;
+    else if (mode == COST_CAUSAL_QUERY) span = min(L, (t + 1) * R);
+    else span = L - t * R;
+    int c = (span + U - 1) / U;
+    return min(c, SCHED_BINS - 1);
+}
+
+__global__ void __launch_bounds__(SCHED_THREADS)
+sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int32_t* __restrict__ hdr,
+             int32_t* __restrict__ tile_off, WorkItem* __restrict__ items) {
+    __shared__ int scan_buf[SCHED_THREADS];
+    __shared__ int bins[SCHED_BINS];
+    const int t = threadIdx.x;
+
+    // 1. tile_off[s] = number of tiles of samples 0..s-1
+    int carry = 0;
+    for (int base = 0; base < B; base += SCHED_THREADS) {
+        int s = base + t;
+        int n = 0;
+        if (s < B) n = (cu[s + 1] - cu[s] + R - 1) / R;
+        int total;
+        int ex = block_exclusive_scan(n, scan_buf, &total);
+        if (s < B) tile_off[s] = carry + ex;
+        carry += total;
+    }
+    const int n_items = carry;
+    if (t == 0) {
+        tile_off[B] = n_items;
+        hdr[0] = n_items;
+    }
+    for (int i = t; i < SCHED_BINS; i += SCHED_THREADS) bins[i] = 0;
+    __syncthreads();  // also makes tile_off (global, written by this block) visible to the block
+
+    // 2. histogram of costs
+    for (int idx = t; idx < n_items; idx += SCHED_THREADS) {
+        int lo = 0, hi = B;  // largest s with tile_off[s] <= idx
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (tile_off[mid] <= idx) lo = mid; else hi = mid;
+        }
+        int L = cu[lo + 1] - cu[lo];
+        atomicAdd(&bins[tile_cost(L, idx - tile_off[lo], R, U, mode)], 1);
+    }
+    __syncthreads();
+
+    // 3. start position of each cost class, heaviest class first
+    {
+        constexpr int PER = SCHED_BINS / SCHED_THREADS;
+        int loc[PER];
+        int sum = 0;
+        for (int i = 0; i < PER; ++i) {  // thread t owns descending costs
+            loc[i] = bins[SCHED_BINS - 1 - (t * PER + i)];
+            sum += loc[i];
+        }
+        int total;
+        int ex = block_exclusive_scan(sum, scan_buf, &total);
+        for (int i = 0; i < PER; ++i) {
+            bins[SCHED_BINS - 1 - (t * PER + i)] = ex;
+            ex += loc[i];
+        }
+    }
+    __syncthreads();
+
+    // 4. scatter (the order inside one cost class is arbitrary; results do not depend on it)
+    for (int idx = t; idx < n_items; idx += SCHED_THREADS) {
+        int lo = 0, hi = B;
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (tile_off[mid] <= idx) lo = mid; else hi = mid;
+        }
+        int begin = cu[lo], end = cu[lo + 1];
+        int tile = idx - tile_off[lo];
+        int pos = atomicAdd(&bins[tile_cost(end - begin, tile, R, U, mode)], 1);
+        items[pos] = make_int4(begin + tile * R, begin, end, tile);
+    }
+}
+
+hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_rows, int partner_rows,
+                            CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream) {
+    char* base = (char*)ws;
+    hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs,
+                       tile_rows, partner_rows, (int)mode, (int32_t*)base,
+                       (int32_t*)(base + lay.tile_off_ofs), (WorkItem*)(base + lay.items_ofs));
+    return hipGetLastError();
+}
+
+}  // namespace va

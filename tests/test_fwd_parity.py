@@ -1,0 +1,113 @@
+"""GPU forward parity: the HIP path through the C ABI against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08962_amd import workloads as W
+from tests._util import LSE_ABS, assert_close, to_f64, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_fwd(w):
+    from paper_2605_08962_amd import binding
+    d = upload(w)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], w.causal, w.scale)
+    torch.cuda.synchronize()
+    return to_f64(o), to_f64(lse)
+
+
+def _check_full(w, allow_output_rounding=False):
+    import oracle
+    print(f"case {w.name} seed={w.seed} B={w.num_seqs} T={w.total_tokens} Hq={w.num_q_heads} "
+          f"Hkv={w.num_kv_heads} D={w.head_dim} causal={w.causal}", flush=True)
+    o, lse = _run_fwd(w)
+    ro, rlse = oracle.fwd(w.f32("q"), w.f32("k"), w.f32("v"), w.cu_seqlens, w.causal, w.scale)
+    assert_close("O", o, ro, allow_output_rounding=allow_output_rounding)
+    if lse.size:
+        assert float(np.abs(lse - rlse).max()) <= LSE_ABS
+
+
+def test_config1_tiny_noncausal():
+    _check_full(W.make(1))
+
+
+@pytest.mark.parametrize("D", [64, 80, 96, 128])
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_multi_tile(D, causal):
+    # spans several 128-row query tiles and 64-row key tiles, with ragged tails and tiny samples
+    w = W.make_custom([300, 1, 129, 64, 0, 513, 7, 128, 65], 4, 4, D, causal, seed=11 + D + causal)
+    _check_full(w)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 128), (6, 1, 64), (32, 8, 128), (4, 4, 80)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_gqa(Hq, Hkv, D, causal):
+    w = W.make_custom([257, 33, 190], Hq, Hkv, D, causal, seed=5 + Hq + D)
+    _check_full(w)
+
+
+@pytest.mark.parametrize("D", [64, 80, 128])
+def test_peaky_softmax(D):
+    # Q scaled by 8 makes rows nearly one-hot and moves the running max often.  Outputs are then
+    # close to single V rows, |O| reaches 4 and more, where bf16 cannot hold a value to 1e-2.
+    w = W.make_custom([400, 90], 2, 2, D, False, seed=21 + D, q_gain=8.0)
+    _check_full(w, allow_output_rounding=True)
+    w = W.make_custom([400, 90], 2, 1, D, True, seed=22 + D, q_gain=8.0)
+    _check_full(w, allow_output_rounding=True)
+
+
+def test_scale_zero_gives_prefix_means():
+    from paper_2605_08962_amd import binding
+    w = W.make_custom([70, 130], 2, 2, 64, True, seed=3)
+    d = upload(w)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], True, 0.0)
+    torch.cuda.synchronize()
+    v = w.f32("v").astype(np.float64)
+    cu = w.cu_seqlens
+    for s in range(2):
+        seg = v[cu[s]:cu[s + 1]]
+        n = np.arange(1, len(seg) + 1)[:, None, None]
+        ref = np.cumsum(seg, 0) / n
+        assert_close("O", to_f64(o)[cu[s]:cu[s + 1]], ref)
+        assert np.abs(to_f64(lse)[:, cu[s]:cu[s + 1]] - np.log(n[:, 0, 0])[None]).max() <= LSE_ABS
+
+
+def test_length_one_returns_v_bit_exact():
+    w = W.make_custom([1] * 9, 4, 2, 128, True, seed=9)
+    o, _ = _run_fwd(w)
+    assert np.array_equal(o, np.repeat(w.f32("v").astype(np.float64), 2, axis=1))
+
+
+def test_packed_equals_alone_and_order_free():
+    from paper_2605_08962_amd import binding
+    w = W.make_custom([200, 64, 333], 4, 2, 64, False, seed=17)
+    d = upload(w)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], False, w.scale)
+    cu = w.cu_seqlens
+    for s in range(3):
+        a, b = int(cu[s]), int(cu[s + 1])
+        one = torch.tensor([0, b - a], dtype=torch.int32, device="cuda")
+        o1, lse1 = binding.varlen_attn_fwd(d["q"][a:b].contiguous(), d["k"][a:b].contiguous(),
+                                           d["v"][a:b].contiguous(), one, False, w.scale)
+        assert torch.equal(o1, o[a:b]) and torch.equal(lse1, lse[:, a:b])
+
+
+def test_empty_inputs_and_errors():
+    from paper_2605_08962_amd import binding
+    q = torch.empty((0, 2, 64), dtype=torch.bfloat16, device="cuda")
+    cu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o, lse = binding.varlen_attn_fwd(q, q, q, cu, False, 0.125)
+    assert o.shape == (0, 2, 64) and lse.shape == (2, 0)
+    q = torch.zeros((8, 2, 48), dtype=torch.bfloat16, device="cuda")
+    cu = torch.tensor([0, 8], dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.VarlenAttnError) as e:
+        binding.varlen_attn_fwd(q, q, q, cu, False, 0.125)
+    assert e.value.status == 3
+    q = torch.zeros((8, 2, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.VarlenAttnError) as e:
+        binding.varlen_attn_fwd(q, q, q, cu, False, -1.0)
+    assert e.value.status == 5
+    with pytest.raises(binding.VarlenAttnError) as e:
+        binding.varlen_attn_fwd(q, q, q, cu, False, 0.125, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 4
