@@ -1,0 +1,131 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/varlen_attn.h declares,
+validates host-visible arguments before touching a device, and sizes its work lists safely.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_08962_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_08962_amd import binding
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "varlen_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(varlen_attn_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_fwd_workspace_bytes",
+            "varlen_attn_bwd_workspace_bytes", "varlen_attn_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_params_struct_matches_header():
+    from paper_2605_08962_amd import binding
+    assert ctypes.sizeof(binding.Params) == 32
+    assert [f[0] for f in binding.Params._fields_] == [
+        "total_tokens", "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "causal", "softmax_scale", "reserved"]
+
+
+def test_status_strings(lib):
+    from paper_2605_08962_amd import binding
+    seen = {binding.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and binding.status_string(0) == "ok"
+    assert binding.status_string(99) == "unknown status"
+
+
+def _call_fwd(lib, p, q=16, k=16, v=16, cu=16, o=16, lse=16, ws=16, ws_bytes=1 << 30):
+    # fake, never dereferenced pointers: every case below must be rejected on the host
+    return lib.varlen_attn_fwd(ctypes.byref(p), q, k, v, cu, o, lse, ws, ws_bytes, None)
+
+
+def test_host_side_validation_needs_no_gpu(lib):
+    from paper_2605_08962_amd import binding
+    mk = binding.make_params
+    assert _call_fwd(lib, mk(0, 0, 2, 2, 64, 0, 0.125)) == 0            # empty: OK, nothing launched
+    assert _call_fwd(lib, mk(0, 3, 2, 2, 64, 0, 0.125)) == 0
+    assert _call_fwd(lib, mk(-1, 1, 2, 2, 64, 0, 0.125)) == 2
+    assert _call_fwd(lib, mk(8, 1, 3, 2, 64, 0, 0.125)) == 2            # Hq % Hkv
+    assert _call_fwd(lib, mk(8, 1, 2, 0, 64, 0, 0.125)) == 2
+    p = mk(8, 1, 2, 2, 64, 0, 0.125); p.causal = 2
+    assert _call_fwd(lib, p) == 2
+    p = mk(8, 1, 2, 2, 64, 0, 0.125); p.reserved = 1
+    assert _call_fwd(lib, p) == 2
+    for d in (0, 32, 48, 72, 256):
+        assert _call_fwd(lib, mk(8, 1, 2, 2, d, 0, 0.125)) == 3
+    for s in (float("nan"), float("inf"), -0.5):
+        assert _call_fwd(lib, mk(8, 1, 2, 2, 64, 0, s)) == 5
+    ok = mk(8, 1, 2, 2, 64, 0, 0.125)
+    assert _call_fwd(lib, ok, q=None) == 1
+    assert _call_fwd(lib, ok, lse=None) == 1
+    assert _call_fwd(lib, ok, k=24) == 7                                 # not 16-byte aligned
+    assert _call_fwd(lib, ok, ws_bytes=8) == 4
+    assert lib.varlen_attn_fwd(None, 16, 16, 16, 16, 16, 16, 16, 64, None) == 1
+    # backward: same order of checks
+    args = [16] * 11
+    assert lib.varlen_attn_bwd(ctypes.byref(mk(8, 1, 2, 2, 64, 0, -1.0)), *args, 1 << 30, None) == 5
+    assert lib.varlen_attn_bwd(ctypes.byref(ok), *args, 8, None) == 4
+    args[9] = None
+    assert lib.varlen_attn_bwd(ctypes.byref(ok), *args, 1 << 30, None) == 1
+    assert lib.varlen_attn_bwd(ctypes.byref(mk(0, 0, 2, 2, 64, 0, 0.125)), *([None] * 11), 0, None) == 0
+
+
+def test_workspace_and_work_list_bounds():
+    from paper_2605_08962_amd import binding
+    rng = np.random.default_rng(0)
+    for trial in range(50):
+        B = int(rng.integers(1, 300))
+        L = rng.integers(0, 700, size=B)
+        if trial % 5 == 0:
+            L[rng.integers(0, B)] = 70000
+        T = int(L.sum())
+        p = binding.make_params(T, B, 8, 2, 128, trial % 2, 0.1)
+        for which, rows in ((0, 128), (1, 128), (2, 128)):
+            need = int(np.sum((L + rows - 1) // rows))
+            cap = binding.max_work_items(p, which)
+            assert need <= cap <= T // rows + B
+        fw, bw = binding.fwd_workspace_bytes(p), binding.bwd_workspace_bytes(p)
+        assert fw >= 64 + 4 * (B + 1) + 16 * binding.max_work_items(p, 0) and fw % 256 == 0
+        assert bw >= 4 * T * 8 + fw
+    assert binding.fwd_workspace_bytes(binding.make_params(8, 1, 2, 2, 72, 0, 0.1)) == 0
+
+
+def test_workload_recipes():
+    w1 = W.make(1, lengths_only=True)
+    assert list(w1.lengths) == [16, 37, 64, 129] and w1.fwd_flops() == 4 * 64 * 2 * 22362
+    w2 = W.make(2, lengths_only=True)
+    assert w2.num_seqs == 64 and w2.lengths.min() >= 256 and w2.lengths.max() <= 9216
+    assert all(int(n) % 4 == 0 for n in w2.lengths)
+    for pos in ("first", "middle", "last"):
+        w3 = W.make(3, lengths_only=True, long_pos=pos)
+        assert w3.num_seqs == 257 and sorted(w3.lengths)[-1] == 65536 and sorted(w3.lengths)[-2] <= 1024
+        assert w3.lengths.min() >= 64
+        assert int(np.argmax(w3.lengths)) == {"first": 0, "middle": 128, "last": 256}[pos]
+    w4 = W.make(4, lengths_only=True)
+    assert w4.total_tokens == 32768 and w4.lengths.min() >= 128 and w4.lengths.max() <= 16384 + 127
+    assert (w4.num_q_heads, w4.num_kv_heads, w4.head_dim, w4.causal) == (32, 8, 128, True)
+    w5 = W.make(5, lengths_only=True)
+    assert np.array_equal(w5.lengths, w2.lengths)
+
+
+def test_bf16_rounding_matches_torch():
+    import torch
+    x = np.random.default_rng(1).standard_normal(100000).astype(np.float32) * 3
+    x[:4] = [1.00390625, 1.01171875, -1.00390625, 0.0]   # ties: to even
+    bits = W.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, ref)
+    assert np.array_equal(W.bf16_bits_to_f32(bits), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
