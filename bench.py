@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the varlen packed attention hot path on one MI355X.
+
+A step is one pass of the whole path on one synthetic batch: forward (scheduler + attention kernel)
+followed by backward (two schedulers, Delta, dK/dV, dQ).  The default workload is the ViT encoder
+layer with dynamic resolution: 64 images of 256..9216 tokens packed non-causally, 16 heads, head_dim
+64, bf16, forward + backward.  Inputs are resident in HBM before the timed region starts.
+
+    python bench.py --gpus 1 --steps 20 --warmup 5
+
+prints one JSON line: useful TFLOP/s of the step (forward 4*D*Hq*sum L^2, backward 2.5x that), the
+roofline record of the kernel that takes the most time, and the CPU oracle timed on a bounded
+sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "varlen attention useful TFLOP/s fwd/bwd on 1 MI355X; % of bf16 MFMA peak"
+PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), or None.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, budget_flops=8e11):
+    """The oracle, as it stands, on whole samples of the batch (shortest first) up to a flop budget."""
+    import oracle
+    from paper_2605_08962_amd import workloads as W
+    order = np.argsort(w.lengths, kind="stable")
+    per = 3.5 * 4.0 * w.head_dim * w.num_q_heads * w.lengths[order].astype(np.float64) ** 2
+    if w.causal:
+        per *= 0.5
+    n = max(1, int(np.searchsorted(np.cumsum(per), budget_flops)))
+    picks = order[:n]
+    cu = w.cu_seqlens.astype(np.int64)
+    idx = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in picks])
+    lens = w.lengths[picks]
+    cu_s = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q, k, v, do = (W.bf16_bits_to_f32(getattr(w, n_)[idx]) for n_ in ("q", "k", "v", "dout"))
+    t0 = time.perf_counter()
+    oracle.fwd(q, k, v, cu_s, w.causal, w.scale)
+    oracle.bwd(q, k, v, do, cu_s, w.causal, w.scale)
+    dt = time.perf_counter() - t0
+    flops = float(per[:n].sum())
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"forward+backward of the {n} shortest samples ({int(lens.sum())} tokens, "
+                      f"{flops:.3e} useful flop) of the same batch, all heads, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5],
+                    help="5 (default): ViT batch forward+backward; 2, 3, 4: forward only on that config")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+                         "use --gpus 1\n")
+        sys.exit(2)
+
+    import torch
+    from paper_2605_08962_amd import binding, workloads as W
+    from tests._util import to_gpu_bf16
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(1)
+    binding.load()
+
+    with_bwd = args.config == 5
+    w = W.make(args.config, with_dout=True)
+    q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
+    cu = torch.from_numpy(w.cu_seqlens).cuda()
+    T = w.total_tokens
+    p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale)
+    o = torch.empty_like(q)
+    lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
+    ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f)
+        if with_bwd:
+            binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
+                                    workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.profile_enable(False)
+    prof = binding.profile_read()
+
+    fwd_flops = w.fwd_flops()
+    step_flops = fwd_flops * (3.5 if with_bwd else 1.0)
+    ms = dt * 1e3 / args.steps
+    value = step_flops / (ms * 1e-3) / 1e12
+
+    # algorithmic flops per launch: forward = F; dK/dV kernel = S, dP, dV, dK = 4 of the backward's 5
+    # GEMMs = 2.0 F; dQ kernel = the dQ GEMM = 0.5 F (its recomputation of S and dP is not counted).
+    algo = {"fwd": fwd_flops, "dkdv": 2.0 * fwd_flops, "dq": 0.5 * fwd_flops}
+    kern = {n: (prof[n][0] / prof[n][1]) for n in algo if prof[n][1] > 0}
+    dom = max(kern, key=lambda n: kern[n] * prof[n][1])
+    achieved = algo[dom] / (kern[dom] * 1e-3) / 1e12
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "num_seqs": w.num_seqs, "total_tokens": T,
+                   "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
+                   "causal": w.causal, "passes": "fwd+bwd" if with_bwd else "fwd", "seed": w.seed},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "kernels_ms": {n: round(prof[n][0] / max(prof[n][1], 1), 4) for n in prof if prof[n][1] > 0},
+        "fwd_tflops": round(fwd_flops / (kern["fwd"] * 1e-3) / 1e12, 2),
+        "roofline": {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dom)},
+    }
+    if with_bwd:
+        bwd_ms = sum(kern[n] for n in ("dkdv", "dq")) + prof["delta"][0] / max(prof["delta"][1], 1)
+        out["bwd_tflops"] = round(2.5 * fwd_flops / (bwd_ms * 1e-3) / 1e12, 2)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -107,6 +107,24 @@ int varlen_attn_last_hip_error(void);
  */
 int64_t varlen_attn_max_work_items(const varlen_attn_params *p, int which);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled (process-wide), every kernel this library
+ * launches is bracketed by two HIP events recorded on the caller's stream; launches are not
+ * synchronised and results are unchanged.  Enabling drops earlier samples.  profile_read() waits
+ * for the recorded events of one kernel kind and returns their summed duration (milliseconds) and
+ * count.  Events are created with hipEventCreate: do not leave this on in a loop that must not
+ * allocate, and read or re-enable now and then so the sample list does not grow without bound.
+ */
+enum {
+    VA_KERNEL_SCHED = 0, /* tile scheduler (1 launch per forward, 2 per backward) */
+    VA_KERNEL_FWD = 1,   /* forward attention */
+    VA_KERNEL_DELTA = 2, /* backward: Delta = rowsum(dO * O) */
+    VA_KERNEL_DKDV = 3,  /* backward: dK, dV */
+    VA_KERNEL_DQ = 4     /* backward: dQ */
+};
+int varlen_attn_profile_enable(int on);
+int varlen_attn_profile_read(int kernel, double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

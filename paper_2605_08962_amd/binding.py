@@ -54,6 +54,11 @@ def load():
     lib.varlen_attn_status_string.restype = ctypes.c_char_p
     lib.varlen_attn_last_hip_error.argtypes = []
     lib.varlen_attn_last_hip_error.restype = ctypes.c_int
+    lib.varlen_attn_profile_enable.argtypes = [ctypes.c_int]
+    lib.varlen_attn_profile_enable.restype = ctypes.c_int
+    lib.varlen_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_int64)]
+    lib.varlen_attn_profile_read.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -147,3 +152,20 @@ def varlen_attn_bwd(dout, q, k, v, out, lse, cu_seqlens, causal, softmax_scale, 
                                dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
                                workspace.numel(), _stream_handle(stream)))
     return dq, dk, dv
+
+
+KERNELS = {"sched": 0, "fwd": 1, "delta": 2, "dkdv": 3, "dq": 4}
+
+
+def profile_enable(on=True):
+    _check(load().varlen_attn_profile_enable(int(bool(on))))
+
+
+def profile_read():
+    """{kernel name: (total milliseconds, launches)} of the launches recorded since profile_enable."""
+    out = {}
+    for name, kid in KERNELS.items():
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(load().varlen_attn_profile_read(kid, ctypes.byref(ms), ctypes.byref(n)))
+        out[name] = (ms.value, n.value)
+    return out

@@ -1,6 +1,8 @@
 // C-ABI entry points of libvarlen_attn.so: argument validation, workspace carving, launches.
 #include <cmath>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "../../include/varlen_attn.h"
 #include "va_internal.h"
@@ -12,6 +14,38 @@ thread_local int g_last_hip_error = 0;
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
     return VA_ERR_HIP;
+}
+
+// Optional per-kernel timing: while enabled, each kernel launch is bracketed by two events recorded
+// on the caller's stream.  Nothing synchronises until varlen_attn_profile_read().
+struct ProfSample { int kernel; hipEvent_t a, b; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfSample> g_prof_samples;
+
+struct ProfScope {
+    bool on = false;
+    ProfSample s{};
+    hipStream_t stream;
+    ProfScope(int kernel, hipStream_t st) : stream(st) {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        if (!g_prof_on) return;
+        if (hipEventCreate(&s.a) != hipSuccess) return;
+        if (hipEventCreate(&s.b) != hipSuccess) { (void)hipEventDestroy(s.a); return; }
+        s.kernel = kernel;
+        on = hipEventRecord(s.a, stream) == hipSuccess;
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(s.b, stream);
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        g_prof_samples.push_back(s);
+    }
+};
+
+void prof_clear_locked() {
+    for (auto& s : g_prof_samples) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+    g_prof_samples.clear();
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -98,9 +132,12 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     if (rc != VA_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    hipError_t e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::FWD_TILE_Q, va::FWD_TILE_KV,
-                                        p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, workspace,
-                                        lay, stream);
+    hipError_t e;
+    {
+        ProfScope ps(VA_KERNEL_SCHED, stream);
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::FWD_TILE_Q, va::FWD_TILE_KV,
+                                 p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, workspace, lay, stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
     va::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
@@ -109,7 +146,10 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     a.max_items = lay.max_items;
     a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
-    e = va::launch_fwd(a, stream);
+    {
+        ProfScope ps(VA_KERNEL_FWD, stream);
+        e = va::launch_fwd(a, stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
     return VA_OK;
 }
@@ -134,13 +174,20 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
 
-    hipError_t e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_KV, va::BWD_STEP_Q,
-                                        p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL,
-                                        ws + lay.kv_ofs, lay.kv, stream);
+    hipError_t e;
+    {
+        ProfScope ps(VA_KERNEL_SCHED, stream);
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_KV, va::BWD_STEP_Q,
+                                 p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL, ws + lay.kv_ofs, lay.kv,
+                                 stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
-    e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_Q, va::BWD_STEP_KV,
-                             p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q,
-                             stream);
+    {
+        ProfScope ps(VA_KERNEL_SCHED, stream);
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_Q, va::BWD_STEP_KV,
+                                 p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q,
+                                 stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
 
     va::BwdArgs a;
@@ -155,11 +202,20 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     a.max_items_q = lay.q.max_items;
     a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
-    e = va::launch_bwd_delta(a, stream);
+    {
+        ProfScope ps(VA_KERNEL_DELTA, stream);
+        e = va::launch_bwd_delta(a, stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
-    e = va::launch_bwd_dkdv(a, stream);
+    {
+        ProfScope ps(VA_KERNEL_DKDV, stream);
+        e = va::launch_bwd_dkdv(a, stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
-    e = va::launch_bwd_dq(a, stream);
+    {
+        ProfScope ps(VA_KERNEL_DQ, stream);
+        e = va::launch_bwd_dq(a, stream);
+    }
     if (e != hipSuccess) return hip_fail(e);
     return VA_OK;
 }
@@ -179,5 +235,32 @@ const char* varlen_attn_status_string(int status) {
 }
 
 int varlen_attn_last_hip_error(void) { return g_last_hip_error; }
+
+int varlen_attn_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (on) prof_clear_locked();
+    g_prof_on = on != 0;
+    return VA_OK;
+}
+
+int varlen_attn_profile_read(int kernel, double* total_ms, int64_t* launches) {
+    if (!total_ms || !launches) return VA_ERR_NULL_PTR;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    double sum = 0.0;
+    int64_t n = 0;
+    for (auto& s : g_prof_samples) {
+        if (s.kernel != kernel) continue;
+        hipError_t e = hipEventSynchronize(s.b);
+        if (e != hipSuccess) return hip_fail(e);
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, s.a, s.b);
+        if (e != hipSuccess) return hip_fail(e);
+        sum += ms;
+        ++n;
+    }
+    *total_ms = sum;
+    *launches = n;
+    return VA_OK;
+}
 
 }  // extern "C"
