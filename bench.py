@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5],
                     help="5 (default): ViT batch forward+backward; 2, 3, 4: forward only on that config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, as the known-size reference that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -94,6 +97,13 @@ def main():
             binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
                                     workspace=ws_b)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.zero_()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
