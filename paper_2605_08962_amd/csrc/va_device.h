@@ -56,6 +56,108 @@ __device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
     return (4 * (lane >> 5) + ((lane & 15) >> 2)) * stride + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 }
 
+// ------------------------------------------------------------------------------------------------
+// LDS tiles filled by direct-to-LDS loads (global_load_lds_dwordx4).
+//
+// Such a load writes the 64 lanes' 16-byte chunks to 1024 CONTIGUOUS LDS bytes, so rows cannot be
+// padded against bank conflicts.  Instead the 16-byte chunks of a row are permuted: logical chunk c
+// of row r lives in slot c ^ swz(r).  swz is chosen so that (a) 16 consecutive rows read at one
+// logical chunk (MFMA A operand read along the row) and (b) 4 consecutive rows read over one
+// 64-byte span (transposing read down the columns) both cover all 64 banks exactly once.
+// Rows are 128 bytes for head_dim 64 and 256 bytes otherwise (head_dim 80 / 96 leave slots unused).
+// ------------------------------------------------------------------------------------------------
+#define VA_GLOBAL __attribute__((address_space(1)))
+
+template <int D>
+struct LdsTile {
+    static constexpr int ROWB = D <= 64 ? 128 : 256;  // bytes per row
+    static constexpr int SLOTS = ROWB / 16;
+    static constexpr int CHUNKS = D / 8;              // slots that hold data
+    static constexpr int RPI = 1024 / ROWB;           // rows one wave-wide load instruction fills
+    __device__ __forceinline__ static int swz(int r) {
+        if (ROWB == 256) return ((r & 3) << 2) | ((r >> 2) & 3);
+        const int x = (r >> 1) & 7;
+        return ((x & 1) << 2) | (x >> 1);
+    }
+    __device__ __forceinline__ static int off(int r, int c) { return r * ROWB + ((c ^ swz(r)) << 4); }
+    // Byte offset this lane passes to lds_read_tr for the 4 x 16 block at rows row0.., columns
+    // 32*db + (0 or 16).. of the tile; row0 must be a multiple of 8 (see tr_lane_offset).
+    __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
+        const int r = row0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
+        const int c = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        return off(r, c) + 8 * (lane & 1);
+    }
+};
+
+// One direct-to-LDS load: every active lane fetches 16 bytes from base + its own byte offset; lane
+// i's data lands at lds_dst + 16 * i (lds_dst is wave-uniform and goes through M0; base is
+// wave-uniform and stays in scalar registers).  Written as inline assembly on purpose: the compiler
+// then does not see an LDS write in flight and so does not put a wait for ALL outstanding loads in
+// front of every LDS read (which is what it does for the equivalent builtin, and which would
+// serialise the prefetch with the compute).  The price is that completion must be waited for by
+// hand (wait_vmcnt) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, unsigned char* lds_dst) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(VA_LDS unsigned char*)lds_dst);
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(sbase) : "memory");
+}
+
+// Per-lane source offsets of the direct-to-LDS loads that fill one LdsTile of ROWS rows of a
+// [rows, heads, D] tensor, split over the 4 waves of the workgroup.  The offsets are relative to
+// the tile's first row; they are computed once per kernel, so that issuing a tile costs no vector
+// ALU work.  `last` holds the offsets for the sample's ragged last tile, where rows past the sample
+// end re-read its last row (finite data that the caller masks).
+template <int D, int ROWS>
+struct TileDma {
+    using T = LdsTile<D>;
+    static constexpr int NI = ROWS / T::RPI / 4;  // load instructions per wave per tile
+    static_assert(ROWS % (T::RPI * 4) == 0, "tile rows must split evenly over 4 waves");
+    uint32_t full[NI], last[NI];
+    bool active[NI];
+    // row_bytes: bytes between consecutive rows of the tensor; L: rows in the sample
+    __device__ __forceinline__ void init(uint32_t row_bytes, int L, int wave, int lane) {
+        const int last_r0 = (L - 1) / ROWS * ROWS;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int blk = wave * NI + i;
+            const int row = blk * T::RPI + lane / T::SLOTS;
+            const int c = (lane % T::SLOTS) ^ T::swz(row);
+            active[i] = T::CHUNKS == T::SLOTS || c < T::CHUNKS;
+            full[i] = (uint32_t)row * row_bytes + c * 16;
+            last[i] = (uint32_t)min(row, L - 1 - last_r0) * row_bytes + c * 16;
+        }
+    }
+    // base: first byte of the sample's row 0 at this head; r0: first row of the tile
+    __device__ __forceinline__ void issue(const unsigned char* base, uint32_t row_bytes, int r0, int L,
+                                          unsigned char* tile, int wave) const {
+        const unsigned char* src = base + (size_t)r0 * row_bytes;
+        const bool ragged = r0 + ROWS > L;  // wave-uniform
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const uint32_t off = ragged ? last[i] : full[i];
+            if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+        }
+    }
+};
+
+// Wait until at most N of this wave's vector-memory loads (direct-to-LDS ones included) are still
+// outstanding; LDS and scalar counters are left alone.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// Workgroup barrier without the memory fence of __syncthreads (which would wait for every
+// outstanding load, including the prefetches that are meant to stay in flight).
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7) {
     bf16x8 r;
     r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;

@@ -5,8 +5,12 @@
 // key rows per 32-key block.  Row max and row sum of the softmax are then lane-local loops
 // plus one exchange between the two wave halves, the running max and the rescale factor are
 // per-lane scalars, and P^T (cast to bf16) already is the B operand of O^T = V^T P^T.  V^T is
-// read from a row-major LDS tile with the transposing LDS read.  K/V tiles of 64 rows are
-// double-buffered in LDS; the next tile's global loads are in flight during the MFMAs.
+// read from a row-major LDS tile with the transposing LDS read.
+//
+// Staging.  K and V tiles of 64 rows go from HBM/L2 straight into LDS (direct-to-LDS loads, no
+// registers in between).  K is triple-buffered and V double-buffered: while tile j is computed,
+// V(j+1) and K(j+2) are in flight, which covers the L2/HBM latency that a one-tile-ahead register
+// prefetch was measured to expose (about a third of the kernel time).
 #include "va_device.h"
 #include "va_internal.h"
 
@@ -14,17 +18,12 @@ namespace va {
 
 template <int D>
 struct FwdCfg {
+    using T = LdsTile<D>;
     static constexpr int BQ = FWD_TILE_Q, BKV = FWD_TILE_KV;
     static constexpr int KS = D / 16;                  // 16-deep steps of QK^T
     static constexpr int DB = (D + 31) / 32;           // 32-wide blocks of O^T rows
-    static constexpr int KSTR = D * 2 + 16;            // LDS bytes per K row (odd multiple of 16)
-    // LDS bytes per V row: smallest size >= DB*64 that is 32 mod 128, which measured fastest for
-    // the transposing reads (rows 4 apart then start 32 banks apart)
-    static constexpr int VSTR = (DB * 64 - 32 + 127) / 128 * 128 + 32;
-    static constexpr int K_BYTES = BKV * KSTR, V_BYTES = BKV * VSTR;
-    static constexpr int CHUNKS_PER_ROW = D / 8;       // 16-byte chunks
-    static constexpr int CHUNKS = BKV * CHUNKS_PER_ROW;
-    static constexpr int LOADS = (CHUNKS + 255) / 256;
+    static constexpr int TILE = BKV * T::ROWB;         // bytes of one K or V tile in LDS
+    static constexpr int NI = TileDma<D, BKV>::NI;     // load instructions per wave per tile
 };
 
 // The running maximum m is only a reference point for the exponentials; it is moved (and O, l
@@ -37,11 +36,14 @@ constexpr float kRescaleLog2 = 8.0f;
 // rows with only a handful of keys live (short samples, the first rows under the causal mask),
 // whose outputs are O(1), so a single bf16 rounding of P would eat most of the 1e-2 tolerance.
 template <int D, bool CAUSAL, bool BOUNDARY>
-__device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigned char* vb, int k_lane,
-                                          int v_lane, const bf16x8 (&qf)[FwdCfg<D>::KS],
+__device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigned char* vb,
+                                          const int (&kaddr)[FwdCfg<D>::KS],
+                                          const int (&vaddr)[FwdCfg<D>::DB][2],
+                                          const bf16x8 (&qf)[FwdCfg<D>::KS],
                                           f32x16 (&oacc)[FwdCfg<D>::DB], float& m, float& lsum,
                                           float c2, int kv0, int L, int qrow, int hh) {
     using C = FwdCfg<D>;
+    constexpr int ROWB = C::T::ROWB;
     f32x16 s[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
@@ -49,7 +51,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            bf16x8 a = *(const bf16x8*)(kb + k_lane + b * 32 * C::KSTR + ks * 32);
+            bf16x8 a = *(const bf16x8*)(kb + kaddr[ks] + b * 32 * ROWB);
             s[b] = mfma32(a, qf[ks], s[b]);
         }
     }
@@ -73,10 +75,24 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         const float alpha = fast_exp2((m - m_new) * c2);
         m = m_new;
         lsum *= alpha;
+        // In-place multiplies (tied operands): written as plain C++ the compiler builds the scaled
+        // accumulators in fresh registers and pays 2 x 16 x DB register copies in EVERY iteration to
+        // merge the two paths, as much as rescaling unconditionally would cost.
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            // (s_nop first: alpha comes straight out of v_exp_f32, and the hardware needs one idle
+            // issue slot between a transcendental op and a consumer the compiler cannot see)
+            asm volatile(
+                "s_nop 1\n\t"
+                "v_mul_f32 %0, %16, %0\n\tv_mul_f32 %1, %16, %1\n\tv_mul_f32 %2, %16, %2\n\tv_mul_f32 %3, %16, %3\n\t"
+                "v_mul_f32 %4, %16, %4\n\tv_mul_f32 %5, %16, %5\n\tv_mul_f32 %6, %16, %6\n\tv_mul_f32 %7, %16, %7\n\t"
+                "v_mul_f32 %8, %16, %8\n\tv_mul_f32 %9, %16, %9\n\tv_mul_f32 %10, %16, %10\n\tv_mul_f32 %11, %16, %11\n\t"
+                "v_mul_f32 %12, %16, %12\n\tv_mul_f32 %13, %16, %13\n\tv_mul_f32 %14, %16, %14\n\tv_mul_f32 %15, %16, %15"
+                : "+v"(oacc[db][0]), "+v"(oacc[db][1]), "+v"(oacc[db][2]), "+v"(oacc[db][3]), "+v"(oacc[db][4]),
+                  "+v"(oacc[db][5]), "+v"(oacc[db][6]), "+v"(oacc[db][7]), "+v"(oacc[db][8]), "+v"(oacc[db][9]),
+                  "+v"(oacc[db][10]), "+v"(oacc[db][11]), "+v"(oacc[db][12]), "+v"(oacc[db][13]),
+                  "+v"(oacc[db][14]), "+v"(oacc[db][15])
+                : "v"(alpha));
     }
     const float mc = m * c2;
     float rs = 0.f;
@@ -108,21 +124,21 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
-                const unsigned char* p0 = vb + v_lane + (32 * b + 16 * st) * C::VSTR + db * 64;
-                bf16x8 a = cat4(lds_read_tr(p0), lds_read_tr(p0 + 8 * C::VSTR));
+                const unsigned char* p0 = vb + (32 * b + 16 * st) * ROWB;
+                bf16x8 a = cat4(lds_read_tr(p0 + vaddr[db][0]), lds_read_tr(p0 + vaddr[db][1]));
                 oacc[db] = mfma32(a, pb[b][st], oacc[db]);
                 if (BOUNDARY) oacc[db] = mfma32(a, plo[b][st], oacc[db]);
             }
 }
 
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, (D <= 64 ? 3 : 2))
 fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
            __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale) {
     using C = FwdCfg<D>;
-    constexpr int BUF = C::K_BYTES + C::V_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+    using LT = LdsTile<D>;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * C::TILE];  // K x3, then V x2
 
     const int item = blockIdx.x / Hq;
     if (item >= hdr[0]) return;
@@ -138,6 +154,47 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const int qrow = q0 + 32 * w + ln;  // this lane's query row inside the sample
     const bool qvalid = qrow < L;
 
+    const int kv_end = CAUSAL ? min(L, q0 + C::BQ) : L;
+    const int ntiles = (kv_end + C::BKV - 1) / C::BKV;
+    // tiles [0, n_plain) need no mask in any wave: whole tiles below the sample end and, under the
+    // causal mask, entirely at or below the tile's first query row
+    const int n_plain = CAUSAL ? min(L, q0 + 1) / C::BKV : L / C::BKV;
+    const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;  // this wave's query rows
+
+    const unsigned char* kbase = (const unsigned char*)(K + ((size_t)sb * Hkv + kvh) * D);
+    const unsigned char* vbase = (const unsigned char*)(V + ((size_t)sb * Hkv + kvh) * D);
+    const uint32_t row_bytes = (uint32_t)Hkv * D * 2;
+    unsigned char* const kbuf = lds;
+    unsigned char* const vbuf = lds + 3 * C::TILE;
+    TileDma<D, C::BKV> dma;  // K and V share the offsets: same shape, same row pitch
+    dma.init(row_bytes, L, w, l);
+    auto load_k = [&](int j, int slot) { dma.issue(kbase, row_bytes, j * C::BKV, L, kbuf + slot * C::TILE, w); };
+    auto load_v = [&](int j, int slot) { dma.issue(vbase, row_bytes, j * C::BKV, L, vbuf + slot * C::TILE, w); };
+
+    // per-lane LDS offsets: K rows read along the row (A operand of S^T), V read down the columns
+    int kaddr[C::KS], vaddr[C::DB][2];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) kaddr[ks] = LT::off(ln, 2 * ks + hh);
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) {
+        vaddr[db][0] = LT::tr_off(l, 0, db);
+        vaddr[db][1] = LT::tr_off(l, 8, db);
+    }
+
+    f32x16 oacc[C::DB];
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+    float m = kMaskedScore, lsum = 0.f;
+    const float c2 = scale * kLog2e;
+
+    // prologue: K(0), V(0), K(1) and this lane's Q fragments.  Everything is waited for here, once:
+    // the compiler cannot see the direct-to-LDS loads, and if the Q loads were still pending in its
+    // bookkeeping at loop entry it would put a wait for ALL outstanding loads into every iteration.
+    load_k(0, 0);
+    load_v(0, 0);
+    if (ntiles > 1) load_k(1, 1);
     bf16x8 qf[C::KS];
     {
         const __bf16* qp = Q + ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
@@ -147,90 +204,43 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
             qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : z;
         }
     }
+    wait_vmcnt<0>();
+    wg_barrier();
 
-    const int kv_end = CAUSAL ? min(L, q0 + C::BQ) : L;
-    const int ntiles = (kv_end + C::BKV - 1) / C::BKV;
-    // tiles [0, n_plain) need no mask in any wave: whole tiles below the sample end and, under the
-    // causal mask, entirely at or below the tile's first query row
-    const int n_plain = CAUSAL ? min(L, q0 + 1) / C::BKV : L / C::BKV;
-    const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;  // this wave's query rows
-
-    // staging: thread -> (row, 16-byte chunk) of the 64-row K and V tiles
-    const __bf16* kbase = K + ((size_t)sb * Hkv + kvh) * D;
-    const __bf16* vbase = V + ((size_t)sb * Hkv + kvh) * D;
-    const size_t row_elems = (size_t)Hkv * D;
-    u32x4 kreg[C::LOADS], vreg[C::LOADS];
-    auto load_tile = [&](int kv0) {
-#pragma unroll
-        for (int i = 0; i < C::LOADS; ++i) {
-            int c = tid + 256 * i;
-            int r = c / C::CHUNKS_PER_ROW, cc = c % C::CHUNKS_PER_ROW;
-            u32x4 z = {0, 0, 0, 0};
-            kreg[i] = z;
-            vreg[i] = z;
-            if (c < C::CHUNKS && kv0 + r < L) {
-                size_t off = (size_t)(kv0 + r) * row_elems + cc * 8;
-                kreg[i] = *(const u32x4*)(kbase + off);
-                vreg[i] = *(const u32x4*)(vbase + off);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        unsigned char* kb = lds + buf * BUF;
-        unsigned char* vb = kb + C::K_BYTES;
-#pragma unroll
-        for (int i = 0; i < C::LOADS; ++i) {
-            int c = tid + 256 * i;
-            int r = c / C::CHUNKS_PER_ROW, cc = c % C::CHUNKS_PER_ROW;
-            if (c < C::CHUNKS) {
-                *(u32x4*)(kb + r * C::KSTR + cc * 16) = kreg[i];
-                *(u32x4*)(vb + r * C::VSTR + cc * 16) = vreg[i];
-            }
-        }
-    };
-    f32x16 oacc[C::DB];
-#pragma unroll
-    for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m = kMaskedScore, lsum = 0.f;
-    const float c2 = scale * kLog2e;
-
-    const int k_lane = ln * C::KSTR + hh * 16;
-    const int v_lane = tr_lane_offset(l, C::VSTR);
-
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
+    int kslot = 0;  // j % 3
     int j = 0;
-    for (; j < n_plain; ++j) {  // no masks, every wave active: no branches around the tile step
-        const bool more = j + 1 < ntiles;
-        if (more) load_tile((j + 1) * C::BKV);
-        const unsigned char* kb = lds + (j & 1) * BUF;
-        tile_step<D, CAUSAL, false>(kb, kb + C::K_BYTES, k_lane, v_lane, qf, oacc, m, lsum, c2,
-                                    j * C::BKV, L, qrow, hh);
-        if (more) store_tile((j + 1) & 1);
-        __syncthreads();
+    // Issue the prefetches of iteration j, return the LDS tiles of iteration j.
+#define VA_FWD_ITER_BEGIN()                                                                \
+        const int kv0 = j * C::BKV;                                                            \
+        if (j + 1 < ntiles) load_v(j + 1, (j + 1) & 1);                                        \
+        if (j + 2 < ntiles) load_k(j + 2, kslot == 0 ? 2 : kslot - 1); /* slot (j + 2) % 3 */ \
+        const unsigned char* kb = kbuf + kslot * C::TILE;                                      \
+        const unsigned char* vb = vbuf + (j & 1) * C::TILE;
+    // K(j+1) and V(j+1) must have landed; K(j+2), issued last, may stay in flight.
+#define VA_FWD_ITER_END()                                                                  \
+        if (j + 2 < ntiles) wait_vmcnt<C::NI>(); else wait_vmcnt<0>();                         \
+        wg_barrier();                                                                          \
+        kslot = kslot == 2 ? 0 : kslot + 1;
+
+    for (; j < n_plain; ++j) {  // no masks, every wave active: nothing conditional around the step
+        VA_FWD_ITER_BEGIN()
+        tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
+        VA_FWD_ITER_END()
     }
     for (; j < ntiles; ++j) {  // the sample's ragged last tile and the causal diagonal
-        const int kv0 = j * C::BKV;
-        const bool more = j + 1 < ntiles;
-        if (more) load_tile(kv0 + C::BKV);
-        const unsigned char* kb = lds + (j & 1) * BUF;
+        VA_FWD_ITER_BEGIN()
         // causal: a wave whose rows all lie above this key tile has nothing to add
         if (!CAUSAL || kv0 <= wq_hi) {
             const bool boundary = (kv0 + C::BKV > L) || (CAUSAL && kv0 + C::BKV - 1 > wq_lo);
             if (boundary)
-                tile_step<D, CAUSAL, true>(kb, kb + C::K_BYTES, k_lane, v_lane, qf, oacc, m, lsum, c2,
-                                           kv0, L, qrow, hh);
+                tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
             else
-                tile_step<D, CAUSAL, false>(kb, kb + C::K_BYTES, k_lane, v_lane, qf, oacc, m, lsum, c2,
-                                            kv0, L, qrow, hh);
+                tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
         }
-        if (more) store_tile((j + 1) & 1);
-        __syncthreads();
+        VA_FWD_ITER_END()
     }
+#undef VA_FWD_ITER_BEGIN
+#undef VA_FWD_ITER_END
 
     // The row sum stays in fp32 on the vector ALU: summing the bf16-rounded P on the matrix cores
     // instead was measured to cost up to 1e-3 in LSE, the whole tolerance.
