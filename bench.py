@@ -26,7 +26,13 @@ sys.path.insert(0, ROOT)
 METRIC = "varlen attention useful TFLOP/s fwd/bwd on 1 MI355X; % of bf16 MFMA peak"
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), or None.
-MEASURED_TRAFFIC_BYTES = {}
+# Read off profiles/bench_vit_d64_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
+# the factors being what the same counters read for a 1 GiB device copy in the same run.
+MEASURED_TRAFFIC_BYTES = {
+    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 8.858e5 + 3.684e5) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 1.052e6 + 7.143e5) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.075e6 + 3.571e5) * 1024),
+}
 
 
 def cpu_baseline(w, budget_flops=8e11):
@@ -139,7 +145,7 @@ def main():
         "fwd_tflops": round(fwd_flops / (kern["fwd"] * 1e-3) / 1e12, 2),
         "roofline": {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dom)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
     }
     if with_bwd:
         bwd_ms = sum(kern[n] for n in ("dkdv", "dq")) + prof["delta"][0] / max(prof["delta"][1], 1)
