@@ -82,7 +82,7 @@ int check_device() {
 
 struct BwdLayout {
     va::SchedLayout kv, q;
-    size_t kv_ofs, q_ofs, delta_ofs, end;
+    size_t kv_ofs, q_ofs, stats_ofs, end;
 };
 
 BwdLayout bwd_layout(const varlen_attn_params* p) {
@@ -91,8 +91,8 @@ BwdLayout bwd_layout(const varlen_attn_params* p) {
     b.q = va::sched_layout(p->total_tokens, p->num_seqs, va::BWD_TILE_Q);
     b.kv_ofs = 0;
     b.q_ofs = b.kv.end_ofs;
-    b.delta_ofs = b.q_ofs + b.q.end_ofs;
-    b.end = b.delta_ofs + ((size_t)p->total_tokens * p->num_q_heads * sizeof(float) + 255) / 256 * 256;
+    b.stats_ofs = b.q_ofs + b.q.end_ofs;
+    b.end = b.stats_ofs + ((size_t)p->total_tokens * p->num_q_heads * 2 * sizeof(float) + 255) / 256 * 256;
     return b;
 }
 
@@ -192,7 +192,7 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
 
     va::BwdArgs a;
     a.dout = dout; a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
-    a.delta = (float*)(ws + lay.delta_ofs);
+    a.stats = (float*)(ws + lay.stats_ofs);
     a.dq = dq; a.dk = dk; a.dv = dv;
     a.sched_hdr_kv = (const int32_t*)(ws + lay.kv_ofs);
     a.items_kv = (const va::WorkItem*)(ws + lay.kv_ofs + lay.kv.items_ofs);

@@ -1,7 +1,7 @@
 // Backward kernels.  P is recomputed from Q, K and the saved LSE (the paper recomputes core
 // attention in the backward pass, Section 5 "Selective Activation Offloading").
 //
-//   delta  : Delta[h,i] = sum_d dO[i,h,d] * O[i,h,d]                       (HBM-bound sweep)
+//   stats  : per (head, row): LSE * log2(e) and Delta = sum_d dO * O        (HBM-bound sweep)
 //   dkdv   : one workgroup per (128-row key tile, kv head); loops over the query heads of the
 //            group and over 64-row query steps; S = Q K^T is kept with one KEY per lane, so
 //            that P and dS are directly the B operands of dV^T += dO^T P and dK^T += Q^T dS
@@ -11,18 +11,21 @@
 //            B operand of dQ^T += K^T dS^T (contraction over key rows).
 // Splitting the backward this way needs no atomics and no fp32 dQ buffer, and the result does not
 // depend on scheduling order; it recomputes S and dP once more than a fused kernel would.
+//
+// Staging is the forward's: 64-row tiles go straight from HBM/L2 into XOR-swizzled LDS tiles with
+// direct-to-LDS loads, three stages deep, one barrier per step, completion tracked with vmcnt.
 #include "va_device.h"
 #include "va_internal.h"
 
 namespace va {
 
 // ------------------------------------------------------------------------------------------------
-// Delta
+// stats[h][i] = { LSE[h][i] * log2(e), sum_d dO[i,h,d] * O[i,h,d] }
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(256)
-delta_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, float* __restrict__ delta,
-             int T, int Hq) {
+stats_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
+             float2* __restrict__ stats, int T, int Hq) {
     // 16 lanes per (token, head) row, one 16-byte chunk each
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
@@ -38,7 +41,7 @@ delta_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, float*
     for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 16);
     if (row < rows && c == 0) {
         const int64_t i = row / Hq, h = row % Hq;
-        delta[h * T + i] = acc;
+        stats[h * T + i] = make_float2(LSE[h * T + i] * kLog2e, acc);
     }
 }
 
@@ -46,54 +49,25 @@ hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream) {
     const int64_t rows = (int64_t)a.total_tokens * a.num_q_heads;
     dim3 grid((unsigned)((rows + 15) / 16)), block(256);
     auto dO = (const __bf16*)a.dout; auto O = (const __bf16*)a.o;
+    auto st = (float2*)a.stats;
     switch (a.head_dim) {
-        case 64: hipLaunchKernelGGL(delta_kernel<64>, grid, block, 0, stream, dO, O, a.delta, a.total_tokens, a.num_q_heads); break;
-        case 80: hipLaunchKernelGGL(delta_kernel<80>, grid, block, 0, stream, dO, O, a.delta, a.total_tokens, a.num_q_heads); break;
-        case 96: hipLaunchKernelGGL(delta_kernel<96>, grid, block, 0, stream, dO, O, a.delta, a.total_tokens, a.num_q_heads); break;
-        case 128: hipLaunchKernelGGL(delta_kernel<128>, grid, block, 0, stream, dO, O, a.delta, a.total_tokens, a.num_q_heads); break;
+        case 64: hipLaunchKernelGGL(stats_kernel<64>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
+        case 80: hipLaunchKernelGGL(stats_kernel<80>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
+        case 96: hipLaunchKernelGGL(stats_kernel<96>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
+        case 128: hipLaunchKernelGGL(stats_kernel<128>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------------------------------------
-// Shared staging of a 64-row [rows, D] tile of a [T, H, D] tensor through registers into LDS.
-// ------------------------------------------------------------------------------------------------
-template <int D>
-struct Stage64 {
-    static constexpr int CPR = D / 8;             // 16-byte chunks per row
-    static constexpr int CHUNKS = 64 * CPR;
-    static constexpr int LOADS = (CHUNKS + 255) / 256;
-    u32x4 reg[LOADS];
-    // rows [r0, r0+64) of the sample, rows >= L read as zero; base points at (sample row 0, head)
-    __device__ __forceinline__ void load(const __bf16* base, size_t row_elems, int r0, int L, int tid) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            int c = tid + 256 * i;
-            int r = c / CPR, cc = c % CPR;
-            u32x4 z = {0, 0, 0, 0};
-            reg[i] = z;
-            if (c < CHUNKS && r0 + r < L) reg[i] = *(const u32x4*)(base + (size_t)(r0 + r) * row_elems + cc * 8);
-        }
-    }
-    __device__ __forceinline__ void store(unsigned char* lds, int stride, int tid) const {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            int c = tid + 256 * i;
-            int r = c / CPR, cc = c % CPR;
-            if (c < CHUNKS) *(u32x4*)(lds + r * stride + cc * 16) = reg[i];
-        }
-    }
-};
-
 template <int D>
 struct BwdCfg {
+    using T = LdsTile<D>;
     static constexpr int KS = D / 16;
     static constexpr int DB = (D + 31) / 32;
-    // LDS bytes per row for tiles read both along rows (16-byte reads) and down columns
-    // (transposing reads); DB * 64 bytes are addressable by the transposing reads.
-    static constexpr int STR = DB * 64 + 16;
-    static constexpr int TILE_BYTES = 64 * STR;
+    static constexpr int TILE = 64 * T::ROWB;        // one 64-row tile in LDS
+    static constexpr int NI = TileDma<D, 64>::NI;    // load instructions per wave per tile
+    static constexpr int STAT_BYTES = 4 * 128;       // per wave: 16 x lse2, 16 x delta
 };
 
 __device__ __forceinline__ bf16x8 pack_regs(const f32x16& x, int st) {
@@ -112,78 +86,83 @@ __device__ __forceinline__ bf16x8 pack_regs_lo(const f32x16& x, int st, bf16x8 h
 // ------------------------------------------------------------------------------------------------
 // One 64-query step for one wave (32 keys).  MASKED steps apply the causal / sample-end mask and
 // carry P and dS as bf16 hi + lo (see the forward kernel for why).
+//   qt, dot : LDS tiles of Q and dO (64 rows);  stat: per 16 rows {16 x lse2, 16 x delta}
+//   aaddr   : per-lane offsets of the row-wise 16-byte reads, taddr: of the transposing reads
 template <int D, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void dkdv_step(const unsigned char* qb_, const unsigned char* dob_,
-                                          const float* lse2_, const float* delta_, int a_lane, int tr_lane,
+__device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigned char* dot,
+                                          const unsigned char* stat, const int (&aaddr)[BwdCfg<D>::KS],
+                                          const int (&taddr)[BwdCfg<D>::DB][2],
                                           const bf16x8 (&kf)[BwdCfg<D>::KS], const bf16x8 (&vf)[BwdCfg<D>::KS],
                                           f32x16 (&dkacc)[BwdCfg<D>::DB], f32x16 (&dvacc)[BwdCfg<D>::DB],
                                           float c2, int q0, int kv, int L, int hh) {
     using C = BwdCfg<D>;
-    f32x16 s[2], dp[2];
+    constexpr int ROWB = C::T::ROWB;
+    // The two 32-query halves of the step are handled one after the other, so that only one half's
+    // scores and dP (2 x 16 registers) are live at a time.
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+        f32x16 s, dp;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[qb][r] = 0.f; dp[qb][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            bf16x8 aq = *(const bf16x8*)(qb_ + a_lane + qb * 32 * C::STR + ks * 32);
-            s[qb] = mfma32(aq, kf[ks], s[qb]);
-            bf16x8 ad = *(const bf16x8*)(dob_ + a_lane + qb * 32 * C::STR + ks * 32);
-            dp[qb] = mfma32(ad, vf[ks], dp[qb]);
+            bf16x8 aq = *(const bf16x8*)(qt + aaddr[ks] + qb * 32 * ROWB);
+            s = mfma32(aq, kf[ks], s);
+            bf16x8 ad = *(const bf16x8*)(dot + aaddr[ks] + qb * 32 * ROWB);
+            dp = mfma32(ad, vf[ks], dp);
         }
-    }
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-            const int qoff = 32 * qb + 8 * r4 + 4 * hh;
-            const float4 l4 = *(const float4*)(lse2_ + qoff);
-            const float4 d4 = *(const float4*)(delta_ + qoff);
+            const int qoff = 32 * qb + 8 * r4 + 4 * hh;  // 4 consecutive query rows, inside one 16-row block
+            const unsigned char* sp = stat + (qoff >> 4) * 128 + (qoff & 15) * 4;
+            const float4 l4 = *(const float4*)(sp);
+            const float4 d4 = *(const float4*)(sp + 64);
             const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
             const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int r = 4 * r4 + e;
-                float p = fast_exp2(__builtin_fmaf(s[qb][r], c2, -lv[e]));
+                float p = fast_exp2(__builtin_fmaf(s[r], c2, -lv[e]));
                 if (MASKED) {
                     const int q = q0 + qoff + e;
                     const bool ok = q < L && kv < L && (!CAUSAL || kv <= q);
                     p = ok ? p : 0.f;
                 }
-                s[qb][r] = p;
-                dp[qb][r] = p * (dp[qb][r] - dv[e]);
+                s[r] = p;
+                dp[r] = p * (dp[r] - dv[e]);
             }
         }
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
         for (int st = 0; st < 2; ++st) {
-            const bf16x8 pb = pack_regs(s[qb], st);
-            const bf16x8 dsb = pack_regs(dp[qb], st);
+            const bf16x8 pb = pack_regs(s, st);
+            const bf16x8 dsb = pack_regs(dp, st);
             bf16x8 pl, dsl;
-            if (MASKED) { pl = pack_regs_lo(s[qb], st, pb); dsl = pack_regs_lo(dp[qb], st, dsb); }
+            if (MASKED) { pl = pack_regs_lo(s, st, pb); dsl = pack_regs_lo(dp, st, dsb); }
+            const int rowoff = (32 * qb + 16 * st) * ROWB;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
-                const int off = tr_lane + (32 * qb + 16 * st) * C::STR + db * 64;
-                bf16x8 ado = cat4(lds_read_tr(dob_ + off), lds_read_tr(dob_ + off + 8 * C::STR));
+                bf16x8 ado = cat4(lds_read_tr(dot + rowoff + taddr[db][0]), lds_read_tr(dot + rowoff + taddr[db][1]));
                 dvacc[db] = mfma32(ado, pb, dvacc[db]);
                 if (MASKED) dvacc[db] = mfma32(ado, pl, dvacc[db]);
-                bf16x8 aq = cat4(lds_read_tr(qb_ + off), lds_read_tr(qb_ + off + 8 * C::STR));
+                bf16x8 aq = cat4(lds_read_tr(qt + rowoff + taddr[db][0]), lds_read_tr(qt + rowoff + taddr[db][1]));
                 dkacc[db] = mfma32(aq, dsb, dkacc[db]);
                 if (MASKED) dkacc[db] = mfma32(aq, dsl, dkacc[db]);
             }
         }
+    }
 }
 
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
-            const __bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
+            const __bf16* __restrict__ dO, const float2* __restrict__ stats,
             __bf16* __restrict__ dK, __bf16* __restrict__ dV, const int32_t* __restrict__ hdr,
             const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale) {
     using C = BwdCfg<D>;
-    constexpr int BUF = 2 * C::TILE_BYTES + 2 * 64 * 4;  // Q tile, dO tile, lse2[64], delta[64]
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+    using LT = LdsTile<D>;
+    constexpr int STAGE = 2 * C::TILE + C::STAT_BYTES;  // Q tile, dO tile, stats
+    constexpr int PER = 2 * C::NI + 1;                  // loads per wave per step
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[3 * STAGE];
 
     const int item = blockIdx.x / Hkv;
     if (item >= hdr[0]) return;
@@ -196,6 +175,51 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const int kv = kv0 + 32 * w + ln;  // this lane's key row inside the sample
     const bool kvalid = kv < L;
 
+    const int first = CAUSAL ? kv0 / BWD_STEP_Q : 0;               // first query step that can see this tile
+    const int nsteps = (L + BWD_STEP_Q - 1) / BWD_STEP_Q - first;  // >= 1 because kv0 < L
+    // Steps [0, n_head) sit on the causal diagonal, steps [n_tail, nsteps) hold the sample's ragged
+    // end (its out-of-range rows are staged as copies of the last row and must be masked); samples
+    // shorter than one step are all "careful".  Steps in between need no mask in any wave.
+    const int n_head = (L < BWD_STEP_Q) ? nsteps : (CAUSAL ? min(2, nsteps) : 0);
+    const int n_tail = max(n_head, nsteps - ((L % BWD_STEP_Q) ? 1 : 0));
+
+    // staging state: the next (head, step) to issue
+    const uint32_t q_row_bytes = (uint32_t)Hq * D * 2;
+    TileDma<D, 64> dma;  // Q and dO share the offsets
+    dma.init(q_row_bytes, L, w, l);
+    // stats: lanes 0..15 fetch lse2, lanes 16..31 delta, of rows 16*w + (lane & 15) of the step
+    const int srow = 16 * w + (l & 15);
+    const int last_q0 = (L - 1) / BWD_STEP_Q * BWD_STEP_Q;
+    const uint32_t stat_full = (uint32_t)srow * 8 + ((l >> 4) & 1) * 4;
+    const uint32_t stat_last = (uint32_t)min(srow, L - 1 - last_q0) * 8 + ((l >> 4) & 1) * 4;
+    int iss_h = 0, iss_s = 0, iss_stage = 0;
+    auto issue_next = [&]() -> bool {  // wave-uniform
+        if (iss_h >= g) return false;
+        const int h = c * g + iss_h;
+        const int q0 = (first + iss_s) * BWD_STEP_Q;
+        unsigned char* stage = lds + iss_stage * STAGE;
+        const unsigned char* sbase = (const unsigned char*)(stats + (size_t)h * T + sb + q0);
+        if (l < 32) dma4(sbase, q0 + BWD_STEP_Q > L ? stat_last : stat_full, stage + 2 * C::TILE + w * 128);
+        dma.issue((const unsigned char*)(Q + ((size_t)sb * Hq + h) * D), q_row_bytes, q0, L, stage, w);
+        dma.issue((const unsigned char*)(dO + ((size_t)sb * Hq + h) * D), q_row_bytes, q0, L, stage + C::TILE, w);
+        if (++iss_s == nsteps) { iss_s = 0; ++iss_h; }
+        iss_stage = iss_stage == 2 ? 0 : iss_stage + 1;
+        return true;
+    };
+
+    int aaddr[C::KS], taddr[C::DB][2];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) aaddr[ks] = LT::off(ln, 2 * ks + hh);
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) {
+        taddr[db][0] = LT::tr_off(l, 0, db);
+        taddr[db][1] = LT::tr_off(l, 8, db);
+    }
+
+    // prologue: two steps in flight plus this lane's K and V fragments; all waited for once (see the
+    // forward kernel for why the register loads must not be left pending at loop entry)
+    issue_next();
+    issue_next();
     bf16x8 kf[C::KS], vf[C::KS];
     {
         const size_t off = ((size_t)(sb + (kvalid ? kv : 0)) * Hkv + c) * D + 8 * hh;
@@ -206,70 +230,60 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
             vf[ks] = kvalid ? *(const bf16x8*)(V + off + 16 * ks) : z;
         }
     }
+    wait_vmcnt<0>();
+    wg_barrier();
+
     f32x16 dkacc[C::DB], dvacc[C::DB];
 #pragma unroll
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
-
-    const int first = CAUSAL ? kv0 / BWD_STEP_Q : 0;          // first query step that can see this tile
-    const int nsteps = (L + BWD_STEP_Q - 1) / BWD_STEP_Q - first;  // >= 1 because kv0 < L
-    const int total = nsteps * g;
-    const size_t q_row_elems = (size_t)Hq * D;
     const float c2 = scale * kLog2e;
-    const int a_lane = ln * C::STR + hh * 16;
-    const int tr_lane = tr_lane_offset(l, C::STR);
     const int wk_lo = kv0 + 32 * w, wk_hi = wk_lo + 31;
 
-    Stage64<D> sq, sdo;
-    float lse_reg = 0.f, delta_reg = 0.f;  // threads 0..63 stage lse2 / delta of one query row each
-    auto load_step = [&](int idx) {
-        const int h = c * g + idx / nsteps;
-        const int q0 = (first + idx % nsteps) * BWD_STEP_Q;
-        sq.load(Q + ((size_t)sb * Hq + h) * D, q_row_elems, q0, L, tid);
-        sdo.load(dO + ((size_t)sb * Hq + h) * D, q_row_elems, q0, L, tid);
-        if (tid < 64) {
-            const bool ok = q0 + tid < L;
-            lse_reg = ok ? LSE[(size_t)h * T + sb + q0 + tid] * kLog2e : 0.f;
-            delta_reg = ok ? Delta[(size_t)h * T + sb + q0 + tid] : 0.f;
+    int stage_i = 0;
+#define VA_DKDV_BEGIN()                                                              \
+        const bool issued = issue_next(); /* step idx + 2 */                             \
+        const unsigned char* b = lds + stage_i * STAGE;                                  \
+        const int q0 = (first + st) * BWD_STEP_Q;
+#define VA_DKDV_END()                                                                \
+        if (issued) wait_vmcnt<PER>(); else wait_vmcnt<0>(); /* step idx + 1 landed */   \
+        wg_barrier();                                                                    \
+        stage_i = stage_i == 2 ? 0 : stage_i + 1;
+#define VA_DKDV_CAREFUL()                                                            \
+        /* causal: a query step entirely above this wave's keys sees none of them */     \
+        if (!CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo) {                                   \
+            const bool masked = (CAUSAL && q0 < wk_hi) || (q0 + BWD_STEP_Q > L);         \
+            if (masked)                                                                  \
+                dkdv_step<D, CAUSAL, true>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
+                                           c2, q0, kv, L, hh);                           \
+            else                                                                         \
+                dkdv_step<D, CAUSAL, false>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
+                                            c2, q0, kv, L, hh);                          \
         }
-    };
-    auto store_step = [&](int buf) {
-        unsigned char* b = lds + buf * BUF;
-        sq.store(b, C::STR, tid);
-        sdo.store(b + C::TILE_BYTES, C::STR, tid);
-        if (tid < 64) {
-            ((float*)(b + 2 * C::TILE_BYTES))[tid] = lse_reg;
-            ((float*)(b + 2 * C::TILE_BYTES))[64 + tid] = delta_reg;
-        }
-    };
 
-    load_step(0);
-    store_step(0);
-    __syncthreads();
-    for (int idx = 0; idx < total; ++idx) {
-        const bool more = idx + 1 < total;
-        if (more) load_step(idx + 1);
-        const unsigned char* b = lds + (idx & 1) * BUF;
-        const float* lse2_ = (const float*)(b + 2 * C::TILE_BYTES);
-        const int q0 = (first + idx % nsteps) * BWD_STEP_Q;
-        // causal: a query step entirely above this wave's keys sees none of them
-        const bool active = !CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo;
-        if (active) {
-            // Rows past the sample end are staged as zeros and end up only in outputs that are
-            // never stored, so the mask is needed under the causal diagonal only; samples shorter
-            // than one step take the careful path too (few keys per row, O(1) gradients).
-            const bool masked = (CAUSAL && q0 < wk_hi) || (L < BWD_STEP_Q);
-            if (masked)
-                dkdv_step<D, CAUSAL, true>(b, b + C::TILE_BYTES, lse2_, lse2_ + 64, a_lane, tr_lane, kf, vf,
-                                           dkacc, dvacc, c2, q0, kv, L, hh);
-            else
-                dkdv_step<D, CAUSAL, false>(b, b + C::TILE_BYTES, lse2_, lse2_ + 64, a_lane, tr_lane, kf, vf,
-                                            dkacc, dvacc, c2, q0, kv, L, hh);
+    for (int hg = 0; hg < g; ++hg) {
+        int st = 0;
+        for (; st < n_head; ++st) {
+            VA_DKDV_BEGIN()
+            VA_DKDV_CAREFUL()
+            VA_DKDV_END()
         }
-        if (more) store_step((idx + 1) & 1);
-        __syncthreads();
+        for (; st < n_tail; ++st) {  // mask-free, every wave active: nothing conditional around the step
+            VA_DKDV_BEGIN()
+            dkdv_step<D, CAUSAL, false>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, c2,
+                                        q0, kv, L, hh);
+            VA_DKDV_END()
+        }
+        for (; st < nsteps; ++st) {
+            VA_DKDV_BEGIN()
+            VA_DKDV_CAREFUL()
+            VA_DKDV_END()
+        }
     }
+#undef VA_DKDV_BEGIN
+#undef VA_DKDV_END
+#undef VA_DKDV_CAREFUL
 
     if (kvalid) {
         __bf16* dkp = dK + ((size_t)(sb + kv) * Hkv + c) * D;
@@ -298,12 +312,13 @@ static hipError_t launch_dkdv_d(const BwdArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(a.max_items_kv * a.num_kv_heads)), block(256);
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
     auto dO = (const __bf16*)a.dout;
+    auto st = (const float2*)a.stats;
     if (a.causal)
-        hipLaunchKernelGGL((dkdv_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, a.lse, a.delta,
+        hipLaunchKernelGGL((dkdv_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
                            a.num_q_heads, a.num_kv_heads, a.scale);
     else
-        hipLaunchKernelGGL((dkdv_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, a.lse, a.delta,
+        hipLaunchKernelGGL((dkdv_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
                            a.num_q_heads, a.num_kv_heads, a.scale);
     return hipGetLastError();
@@ -323,11 +338,13 @@ hipError_t launch_bwd_dkdv(const BwdArgs& a, hipStream_t stream) {
 // dQ
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void dq_step(const unsigned char* kb_, const unsigned char* vb_, int a_lane,
-                                        int tr_lane, const bf16x8 (&qf)[BwdCfg<D>::KS],
-                                        const bf16x8 (&dof)[BwdCfg<D>::KS], f32x16 (&dqacc)[BwdCfg<D>::DB],
-                                        float c2, float lse2, float delta, int kv0, int qrow, int L, int hh) {
+__device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned char* vt,
+                                        const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
+                                        const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
+                                        f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float delta,
+                                        int kv0, int qrow, int L, int hh) {
     using C = BwdCfg<D>;
+    constexpr int ROWB = C::T::ROWB;
     f32x16 s[2], dp[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
@@ -335,9 +352,9 @@ __device__ __forceinline__ void dq_step(const unsigned char* kb_, const unsigned
         for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            bf16x8 ak = *(const bf16x8*)(kb_ + a_lane + b * 32 * C::STR + ks * 32);
+            bf16x8 ak = *(const bf16x8*)(kt + aaddr[ks] + b * 32 * ROWB);
             s[b] = mfma32(ak, qf[ks], s[b]);
-            bf16x8 av = *(const bf16x8*)(vb_ + a_lane + b * 32 * C::STR + ks * 32);
+            bf16x8 av = *(const bf16x8*)(vt + aaddr[ks] + b * 32 * ROWB);
             dp[b] = mfma32(av, dof[ks], dp[b]);
         }
     }
@@ -360,10 +377,10 @@ __device__ __forceinline__ void dq_step(const unsigned char* kb_, const unsigned
             const bf16x8 dsb = pack_regs(dp[b], st);
             bf16x8 dsl;
             if (MASKED) dsl = pack_regs_lo(dp[b], st, dsb);
+            const int rowoff = (32 * b + 16 * st) * ROWB;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
-                const int off = tr_lane + (32 * b + 16 * st) * C::STR + db * 64;
-                bf16x8 ak = cat4(lds_read_tr(kb_ + off), lds_read_tr(kb_ + off + 8 * C::STR));
+                bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
                 dqacc[db] = mfma32(ak, dsb, dqacc[db]);
                 if (MASKED) dqacc[db] = mfma32(ak, dsl, dqacc[db]);
             }
@@ -371,14 +388,15 @@ __device__ __forceinline__ void dq_step(const unsigned char* kb_, const unsigned
 }
 
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
+__global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
-          const __bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
+          const __bf16* __restrict__ dO, const float2* __restrict__ stats,
           __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
           int T, int Hq, int Hkv, float scale) {
     using C = BwdCfg<D>;
-    constexpr int BUF = 2 * C::TILE_BYTES;  // K tile, V tile
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+    using LT = LdsTile<D>;
+    constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[3 * STAGE];
 
     const int item = blockIdx.x / Hq;
     if (item >= hdr[0]) return;
@@ -392,6 +410,30 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     const int qrow = q0 + 32 * w + ln;
     const bool qvalid = qrow < L;
 
+    const int kv_end = CAUSAL ? min(L, q0 + BWD_TILE_Q) : L;
+    const int nsteps = (kv_end + BWD_STEP_KV - 1) / BWD_STEP_KV;
+    const int n_plain = CAUSAL ? min(L, q0 + 1) / BWD_STEP_KV : L / BWD_STEP_KV;
+    const unsigned char* kbase = (const unsigned char*)(K + ((size_t)sb * Hkv + kvh) * D);
+    const unsigned char* vbase = (const unsigned char*)(V + ((size_t)sb * Hkv + kvh) * D);
+    const uint32_t row_bytes = (uint32_t)Hkv * D * 2;
+    TileDma<D, 64> dma;
+    dma.init(row_bytes, L, w, l);
+    auto load_kv = [&](int j, int stage) {
+        dma.issue(kbase, row_bytes, j * BWD_STEP_KV, L, lds + stage * STAGE, w);
+        dma.issue(vbase, row_bytes, j * BWD_STEP_KV, L, lds + stage * STAGE + C::TILE, w);
+    };
+
+    int aaddr[C::KS], taddr[C::DB][2];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) aaddr[ks] = LT::off(ln, 2 * ks + hh);
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) {
+        taddr[db][0] = LT::tr_off(l, 0, db);
+        taddr[db][1] = LT::tr_off(l, 8, db);
+    }
+
+    load_kv(0, 0);
+    if (nsteps > 1) load_kv(1, 1);
     bf16x8 qf[C::KS], dof[C::KS];
     float lse2 = 0.f, delta = 0.f;
     {
@@ -403,57 +445,51 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
             dof[ks] = qvalid ? *(const bf16x8*)(dO + off + 16 * ks) : z;
         }
         if (qvalid) {
-            lse2 = LSE[(size_t)h * T + sb + qrow] * kLog2e;
-            delta = Delta[(size_t)h * T + sb + qrow];
+            const float2 st = stats[(size_t)h * T + sb + qrow];
+            lse2 = st.x;
+            delta = st.y;
         }
     }
+    wait_vmcnt<0>();
+    wg_barrier();
+
     f32x16 dqacc[C::DB];
 #pragma unroll
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) dqacc[db][r] = 0.f;
-
-    const int kv_end = CAUSAL ? min(L, q0 + BWD_TILE_Q) : L;
-    const int nsteps = (kv_end + BWD_STEP_KV - 1) / BWD_STEP_KV;
-    const size_t kv_row_elems = (size_t)Hkv * D;
-    const __bf16* kbase = K + ((size_t)sb * Hkv + kvh) * D;
-    const __bf16* vbase = V + ((size_t)sb * Hkv + kvh) * D;
     const float c2 = scale * kLog2e;
-    const int a_lane = ln * C::STR + hh * 16;
-    const int tr_lane = tr_lane_offset(l, C::STR);
     const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;
 
-    Stage64<D> sk, sv;
-    sk.load(kbase, kv_row_elems, 0, L, tid);
-    sv.load(vbase, kv_row_elems, 0, L, tid);
-    sk.store(lds, C::STR, tid);
-    sv.store(lds + C::TILE_BYTES, C::STR, tid);
-    __syncthreads();
-    for (int j = 0; j < nsteps; ++j) {
-        const int kv0 = j * BWD_STEP_KV;
-        const bool more = j + 1 < nsteps;
-        if (more) {
-            sk.load(kbase, kv_row_elems, kv0 + BWD_STEP_KV, L, tid);
-            sv.load(vbase, kv_row_elems, kv0 + BWD_STEP_KV, L, tid);
-        }
-        const unsigned char* b = lds + (j & 1) * BUF;
-        const bool active = !CAUSAL || kv0 <= wq_hi;
-        if (active) {
+    int stage_i = 0;
+    int j = 0;
+#define VA_DQ_BEGIN()                                                                     \
+        const int kv0 = j * BWD_STEP_KV;                                                      \
+        if (j + 2 < nsteps) load_kv(j + 2, stage_i == 0 ? 2 : stage_i - 1);                   \
+        const unsigned char* b = lds + stage_i * STAGE;
+#define VA_DQ_END()                                                                       \
+        if (j + 2 < nsteps) wait_vmcnt<2 * C::NI>(); else wait_vmcnt<0>();                    \
+        wg_barrier();                                                                         \
+        stage_i = stage_i == 2 ? 0 : stage_i + 1;
+
+    for (; j < n_plain; ++j) {
+        VA_DQ_BEGIN()
+        dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
+        VA_DQ_END()
+    }
+    for (; j < nsteps; ++j) {
+        VA_DQ_BEGIN()
+        if (!CAUSAL || kv0 <= wq_hi) {
             const bool masked = (kv0 + BWD_STEP_KV > L) || (CAUSAL && kv0 + BWD_STEP_KV - 1 > wq_lo);
             if (masked)
-                dq_step<D, CAUSAL, true>(b, b + C::TILE_BYTES, a_lane, tr_lane, qf, dof, dqacc, c2, lse2, delta,
-                                         kv0, qrow, L, hh);
+                dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
             else
-                dq_step<D, CAUSAL, false>(b, b + C::TILE_BYTES, a_lane, tr_lane, qf, dof, dqacc, c2, lse2, delta,
-                                          kv0, qrow, L, hh);
+                dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
         }
-        if (more) {
-            unsigned char* nb = lds + ((j + 1) & 1) * BUF;
-            sk.store(nb, C::STR, tid);
-            sv.store(nb + C::TILE_BYTES, C::STR, tid);
-        }
-        __syncthreads();
+        VA_DQ_END()
     }
+#undef VA_DQ_BEGIN
+#undef VA_DQ_END
 
     if (qvalid) {
         __bf16* dqp = dQ + ((size_t)(sb + qrow) * Hq + h) * D;
@@ -477,12 +513,13 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(a.max_items_q * a.num_q_heads)), block(256);
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
     auto dO = (const __bf16*)a.dout;
+    auto st = (const float2*)a.stats;
     if (a.causal)
-        hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, a.lse, a.delta,
+        hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale);
     else
-        hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, a.lse, a.delta,
+        hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale);
     return hipGetLastError();

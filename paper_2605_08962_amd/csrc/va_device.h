@@ -105,6 +105,16 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, unsig
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(sbase) : "memory");
 }
 
+// Same with 4 bytes per lane: lane i's dword lands at lds_dst + 4 * i.
+__device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, unsigned char* lds_dst) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(VA_LDS unsigned char*)lds_dst);
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" : : "s"(m0), "v"(byte_off), "s"(sbase) : "memory");
+}
+
 // Per-lane source offsets of the direct-to-LDS loads that fill one LdsTile of ROWS rows of a
 // [rows, heads, D] tensor, split over the 4 waves of the workgroup.  The offsets are relative to
 // the tile's first row; they are computed once per kernel, so that issuing a tile costs no vector

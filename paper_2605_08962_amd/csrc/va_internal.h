@@ -49,7 +49,7 @@ hipError_t launch_fwd(const FwdArgs& a, hipStream_t stream);
 struct BwdArgs {
     const void *dout, *q, *k, *v, *o;
     const float* lse;
-    float* delta;  // fp32 [Hq, T] scratch
+    float* stats;  // fp32 [Hq, T, 2] scratch: LSE * log2(e) and Delta per (head, row)
     void *dq, *dk, *dv;
     const int32_t* sched_hdr_kv;
     const WorkItem* items_kv;
