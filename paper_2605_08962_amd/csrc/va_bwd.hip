@@ -101,6 +101,9 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
     // scores and dP (2 x 16 registers) are live at a time.
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+        // keep the instruction scheduler from hoisting the second half's LDS reads over the first
+        // half: it would hold both halves' operands in registers and spill
+        if (qb) __builtin_amdgcn_sched_barrier(0);
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -239,7 +242,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
     const float c2 = scale * kLog2e;
-    const int wk_lo = kv0 + 32 * w, wk_hi = wk_lo + 31;
+    const int wk_lo = kv0 + 32 * w;
 
     int stage_i = 0;
 #define VA_DKDV_BEGIN()                                                              \
@@ -251,16 +254,11 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         wg_barrier();                                                                    \
         stage_i = stage_i == 2 ? 0 : stage_i + 1;
 #define VA_DKDV_CAREFUL()                                                            \
-        /* causal: a query step entirely above this wave's keys sees none of them */     \
-        if (!CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo) {                                   \
-            const bool masked = (CAUSAL && q0 < wk_hi) || (q0 + BWD_STEP_Q > L);         \
-            if (masked)                                                                  \
-                dkdv_step<D, CAUSAL, true>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
-                                           c2, q0, kv, L, hh);                           \
-            else                                                                         \
-                dkdv_step<D, CAUSAL, false>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
-                                            c2, q0, kv, L, hh);                          \
-        }
+        /* causal: a query step entirely above this wave's keys sees none of them; every other  \
+           step here takes the masked variant (a superset of the plain one) to keep code small */ \
+        if (!CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo)                                     \
+            dkdv_step<D, CAUSAL, true>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
+                                       c2, q0, kv, L, hh);
 
     for (int hg = 0; hg < g; ++hg) {
         int st = 0;
@@ -459,7 +457,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 #pragma unroll
         for (int r = 0; r < 16; ++r) dqacc[db][r] = 0.f;
     const float c2 = scale * kLog2e;
-    const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;
+    const int wq_hi = q0 + 32 * w + 31;
 
     int stage_i = 0;
     int j = 0;
@@ -479,13 +477,10 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     }
     for (; j < nsteps; ++j) {
         VA_DQ_BEGIN()
-        if (!CAUSAL || kv0 <= wq_hi) {
-            const bool masked = (kv0 + BWD_STEP_KV > L) || (CAUSAL && kv0 + BWD_STEP_KV - 1 > wq_lo);
-            if (masked)
-                dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
-            else
-                dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
-        }
+        // causal: a wave whose rows all lie above this key step has nothing to add; every other step
+        // here takes the masked variant (a superset of the plain one) to keep the code small
+        if (!CAUSAL || kv0 <= wq_hi)
+            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
         VA_DQ_END()
     }
 #undef VA_DQ_BEGIN
