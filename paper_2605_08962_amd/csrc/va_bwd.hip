@@ -1,7 +1,7 @@
 // Backward kernels.  P is recomputed from Q, K and the saved LSE (the paper recomputes core
 // attention in the backward pass, Section 5 "Selective Activation Offloading").
 //
-//   stats  : per (head, row): LSE * log2(e) and Delta = sum_d dO * O        (HBM-bound sweep)
+//   stats  : per (head, row): LSE * log2(e) and -Delta = -sum_d dO * O      (HBM-bound sweep)
 //   dkdv   : one workgroup per (128-row key tile, kv head); loops over the query heads of the
 //            group and over 64-row query steps; S = Q K^T is kept with one KEY per lane, so
 //            that P and dS are directly the B operands of dV^T += dO^T P and dK^T += Q^T dS
@@ -20,7 +20,9 @@
 namespace va {
 
 // ------------------------------------------------------------------------------------------------
-// stats[h][i] = { LSE[h][i] * log2(e), sum_d dO[i,h,d] * O[i,h,d] }
+// stats[h][i] = { LSE[h][i] * log2(e), -sum_d dO[i,h,d] * O[i,h,d] }
+// (Delta is stored negated so that the dK/dV kernel can load it straight into the accumulator of
+// dP = dO V^T and get dP - Delta out of the MFMA for free.)
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(256)
@@ -41,7 +43,7 @@ stats_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const 
     for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 16);
     if (row < rows && c == 0) {
         const int64_t i = row / Hq, h = row % Hq;
-        stats[h * T + i] = make_float2(LSE[h * T + i] * kLog2e, acc);
+        stats[h * T + i] = make_float2(LSE[h * T + i] * kLog2e, -acc);
     }
 }
 
@@ -105,8 +107,19 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
         // half: it would hold both halves' operands in registers and spill
         if (qb) __builtin_amdgcn_sched_barrier(0);
         f32x16 s, dp;
+        float lv[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int qoff = 32 * qb + 8 * r4 + 4 * hh;  // 4 consecutive query rows, inside one 16-row block
+            const unsigned char* sp = stat + (qoff >> 4) * 128 + (qoff & 15) * 4;
+            const float4 l4 = *(const float4*)(sp);
+            const float4 d4 = *(const float4*)(sp + 64);
+            lv[4 * r4 + 0] = l4.x; lv[4 * r4 + 1] = l4.y; lv[4 * r4 + 2] = l4.z; lv[4 * r4 + 3] = l4.w;
+            // dP accumulates on top of -Delta
+            dp[4 * r4 + 0] = d4.x; dp[4 * r4 + 1] = d4.y; dp[4 * r4 + 2] = d4.z; dp[4 * r4 + 3] = d4.w;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
             bf16x8 aq = *(const bf16x8*)(qt + aaddr[ks] + qb * 32 * ROWB);
@@ -115,25 +128,15 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
             dp = mfma32(ad, vf[ks], dp);
         }
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const int qoff = 32 * qb + 8 * r4 + 4 * hh;  // 4 consecutive query rows, inside one 16-row block
-            const unsigned char* sp = stat + (qoff >> 4) * 128 + (qoff & 15) * 4;
-            const float4 l4 = *(const float4*)(sp);
-            const float4 d4 = *(const float4*)(sp + 64);
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-            const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r = 4 * r4 + e;
-                float p = fast_exp2(__builtin_fmaf(s[r], c2, -lv[e]));
-                if (MASKED) {
-                    const int q = q0 + qoff + e;
-                    const bool ok = q < L && kv < L && (!CAUSAL || kv <= q);
-                    p = ok ? p : 0.f;
-                }
-                s[r] = p;
-                dp[r] = p * (dp[r] - dv[e]);
+        for (int r = 0; r < 16; ++r) {
+            float p = fast_exp2(__builtin_fmaf(s[r], c2, -lv[r]));
+            if (MASKED) {
+                const int q = q0 + 32 * qb + 8 * (r / 4) + 4 * hh + (r % 4);
+                const bool ok = q < L && kv < L && (!CAUSAL || kv <= q);
+                p = ok ? p : 0.f;
             }
+            s[r] = p;
+            dp[r] = p * dp[r];
         }
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
@@ -172,9 +175,11 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const int c = blockIdx.x % Hkv;
     const int g = Hq / Hkv;
     const WorkItem it = items[item];
-    const int sb = it.y, L = it.z - it.y, kv0 = it.x - it.y;
+    // same for the whole workgroup: tell the compiler, so that everything derived stays in SGPRs
+    const int sb = __builtin_amdgcn_readfirstlane(it.y), L = __builtin_amdgcn_readfirstlane(it.z - it.y),
+              kv0 = __builtin_amdgcn_readfirstlane(it.x - it.y);
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 31, hh = l >> 5;
+    const int tid = threadIdx.x, w = uniform_wave_id(), l = tid & 63, ln = l & 31, hh = l >> 5;
     const int kv = kv0 + 32 * w + ln;  // this lane's key row inside the sample
     const bool kvalid = kv < L;
 
@@ -196,11 +201,12 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const uint32_t stat_full = (uint32_t)srow * 8 + ((l >> 4) & 1) * 4;
     const uint32_t stat_last = (uint32_t)min(srow, L - 1 - last_q0) * 8 + ((l >> 4) & 1) * 4;
     int iss_h = 0, iss_s = 0, iss_stage = 0;
+    const uint32_t lds0 = lds_address(lds);
     auto issue_next = [&]() -> bool {  // wave-uniform
         if (iss_h >= g) return false;
         const int h = c * g + iss_h;
         const int q0 = (first + iss_s) * BWD_STEP_Q;
-        unsigned char* stage = lds + iss_stage * STAGE;
+        const uint32_t stage = lds0 + iss_stage * STAGE;
         const unsigned char* sbase = (const unsigned char*)(stats + (size_t)h * T + sb + q0);
         if (l < 32) dma4(sbase, q0 + BWD_STEP_Q > L ? stat_last : stat_full, stage + 2 * C::TILE + w * 128);
         dma.issue((const unsigned char*)(Q + ((size_t)sb * Hq + h) * D), q_row_bytes, q0, L, stage, w);
@@ -339,7 +345,7 @@ template <int D, bool CAUSAL, bool MASKED>
 __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned char* vt,
                                         const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
                                         const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
-                                        f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float delta,
+                                        f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
                                         int kv0, int qrow, int L, int hh) {
     using C = BwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
@@ -366,7 +372,7 @@ __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned 
                 const bool ok = kv < L && qrow < L && (!CAUSAL || kv <= qrow);
                 p = ok ? p : 0.f;
             }
-            dp[b][r] = p * (dp[b][r] - delta);
+            dp[b][r] = p * (dp[b][r] + ndelta);
         }
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -402,9 +408,11 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
-    const int sb = it.y, L = it.z - it.y, q0 = it.x - it.y;
+    // same for the whole workgroup: tell the compiler, so that everything derived stays in SGPRs
+    const int sb = __builtin_amdgcn_readfirstlane(it.y), L = __builtin_amdgcn_readfirstlane(it.z - it.y),
+              q0 = __builtin_amdgcn_readfirstlane(it.x - it.y);
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 31, hh = l >> 5;
+    const int tid = threadIdx.x, w = uniform_wave_id(), l = tid & 63, ln = l & 31, hh = l >> 5;
     const int qrow = q0 + 32 * w + ln;
     const bool qvalid = qrow < L;
 
@@ -416,9 +424,10 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     const uint32_t row_bytes = (uint32_t)Hkv * D * 2;
     TileDma<D, 64> dma;
     dma.init(row_bytes, L, w, l);
+    const uint32_t lds0 = lds_address(lds);
     auto load_kv = [&](int j, int stage) {
-        dma.issue(kbase, row_bytes, j * BWD_STEP_KV, L, lds + stage * STAGE, w);
-        dma.issue(vbase, row_bytes, j * BWD_STEP_KV, L, lds + stage * STAGE + C::TILE, w);
+        dma.issue(kbase, row_bytes, j * BWD_STEP_KV, L, lds0 + stage * STAGE, w);
+        dma.issue(vbase, row_bytes, j * BWD_STEP_KV, L, lds0 + stage * STAGE + C::TILE, w);
     };
 
     int aaddr[C::KS], taddr[C::DB][2];
@@ -433,7 +442,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     load_kv(0, 0);
     if (nsteps > 1) load_kv(1, 1);
     bf16x8 qf[C::KS], dof[C::KS];
-    float lse2 = 0.f, delta = 0.f;
+    float lse2 = 0.f, ndelta = 0.f;  // ndelta = -Delta
     {
         const size_t off = ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
 #pragma unroll
@@ -445,7 +454,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
         if (qvalid) {
             const float2 st = stats[(size_t)h * T + sb + qrow];
             lse2 = st.x;
-            delta = st.y;
+            ndelta = st.y;
         }
     }
     wait_vmcnt<0>();
@@ -472,7 +481,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 
     for (; j < n_plain; ++j) {
         VA_DQ_BEGIN()
-        dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
+        dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh);
         VA_DQ_END()
     }
     for (; j < nsteps; ++j) {
@@ -480,7 +489,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
         // causal: a wave whose rows all lie above this key step has nothing to add; every other step
         // here takes the masked variant (a superset of the plain one) to keep the code small
         if (!CAUSAL || kv0 <= wq_hi)
-            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, delta, kv0, qrow, L, hh);
+            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh);
         VA_DQ_END()
     }
 #undef VA_DQ_BEGIN

@@ -90,30 +90,35 @@ struct LdsTile {
 };
 
 // One direct-to-LDS load: every active lane fetches 16 bytes from base + its own byte offset; lane
-// i's data lands at lds_dst + 16 * i (lds_dst is wave-uniform and goes through M0; base is
-// wave-uniform and stays in scalar registers).  Written as inline assembly on purpose: the compiler
+// i's data lands at lds_addr + 16 * i (lds_addr is a wave-uniform LDS byte address and goes through
+// M0; base is wave-uniform and stays in scalar registers).  Written as inline assembly on purpose: the compiler
 // then does not see an LDS write in flight and so does not put a wait for ALL outstanding loads in
 // front of every LDS read (which is what it does for the equivalent builtin, and which would
 // serialise the prefetch with the compute).  The price is that completion must be waited for by
 // hand (wait_vmcnt) before the barrier that publishes the tile.
-__device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, unsigned char* lds_dst) {
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(VA_LDS unsigned char*)lds_dst);
-    const uint64_t b = (uint64_t)(uintptr_t)base;
+// (readfirstlane of a value the compiler already knows to be uniform folds away; it is there for the
+// cases it cannot prove, because an "s" operand must never be handed a vector register)
+__device__ __forceinline__ uint64_t uniform_u64(const void* p) {
+    const uint64_t b = (uint64_t)(uintptr_t)p;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    const uint64_t sbase = ((uint64_t)hi << 32) | lo;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(sbase) : "memory");
+    return ((uint64_t)hi << 32) | lo;
 }
-
-// Same with 4 bytes per lane: lane i's dword lands at lds_dst + 4 * i.
-__device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, unsigned char* lds_dst) {
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(VA_LDS unsigned char*)lds_dst);
-    const uint64_t b = (uint64_t)(uintptr_t)base;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    const uint64_t sbase = ((uint64_t)hi << 32) | lo;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" : : "s"(m0), "v"(byte_off), "s"(sbase) : "memory");
+__device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory");
 }
+// Same with 4 bytes per lane: lane i's dword lands at lds_addr + 4 * i.
+__device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
+                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory");
+}
+// LDS byte address (what M0 and ds instructions use) of a pointer into a __shared__ array.
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(VA_LDS const unsigned char*)p;
+}
+// Index of this wave inside its workgroup, as a value the compiler knows to be wave-uniform.
+__device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Per-lane source offsets of the direct-to-LDS loads that fill one LdsTile of ROWS rows of a
 // [rows, heads, D] tensor, split over the 4 waves of the workgroup.  The offsets are relative to
@@ -140,9 +145,10 @@ struct TileDma {
             last[i] = (uint32_t)min(row, L - 1 - last_r0) * row_bytes + c * 16;
         }
     }
-    // base: first byte of the sample's row 0 at this head; r0: first row of the tile
+    // base: first byte of the sample's row 0 at this head; r0: first row of the tile; tile: LDS byte
+    // address of the tile; wave: uniform_wave_id()
     __device__ __forceinline__ void issue(const unsigned char* base, uint32_t row_bytes, int r0, int L,
-                                          unsigned char* tile, int wave) const {
+                                          uint32_t tile, int wave) const {
         const unsigned char* src = base + (size_t)r0 * row_bytes;
         const bool ragged = r0 + ROWS > L;  // wave-uniform
 #pragma unroll

@@ -148,9 +148,11 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
-    const int sb = it.y, L = it.z - it.y, q0 = it.x - it.y;  // q0: tile start inside the sample
+    // same for the whole workgroup: tell the compiler, so that everything derived stays in SGPRs
+    const int sb = __builtin_amdgcn_readfirstlane(it.y), L = __builtin_amdgcn_readfirstlane(it.z - it.y),
+              q0 = __builtin_amdgcn_readfirstlane(it.x - it.y);  // q0: tile start inside the sample
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 31, hh = l >> 5;
+    const int tid = threadIdx.x, w = uniform_wave_id(), l = tid & 63, ln = l & 31, hh = l >> 5;
     const int qrow = q0 + 32 * w + ln;  // this lane's query row inside the sample
     const bool qvalid = qrow < L;
 
@@ -168,8 +170,9 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     unsigned char* const vbuf = lds + 3 * C::TILE;
     TileDma<D, C::BKV> dma;  // K and V share the offsets: same shape, same row pitch
     dma.init(row_bytes, L, w, l);
-    auto load_k = [&](int j, int slot) { dma.issue(kbase, row_bytes, j * C::BKV, L, kbuf + slot * C::TILE, w); };
-    auto load_v = [&](int j, int slot) { dma.issue(vbase, row_bytes, j * C::BKV, L, vbuf + slot * C::TILE, w); };
+    const uint32_t lds0 = lds_address(lds);
+    auto load_k = [&](int j, int slot) { dma.issue(kbase, row_bytes, j * C::BKV, L, lds0 + slot * C::TILE, w); };
+    auto load_v = [&](int j, int slot) { dma.issue(vbase, row_bytes, j * C::BKV, L, lds0 + (3 + slot) * C::TILE, w); };
 
     // per-lane LDS offsets: K rows read along the row (A operand of S^T), V read down the columns
     int kaddr[C::KS], vaddr[C::DB][2];
