@@ -19,6 +19,13 @@
 
 namespace va {
 
+#ifdef VA_PHASE_CLOCKS
+__device__ unsigned long long g_phase[16];
+#define VA_CLK(i) { long long t_ = __builtin_readcyclecounter(); clk[i] += t_ - tprev; tprev = t_; }
+#else
+#define VA_CLK(i)
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // stats[h][i] = { LSE[h][i] * log2(e), -sum_d dO[i,h,d] * O[i,h,d] }
 // (Delta is stored negated so that the dK/dV kernel can load it straight into the accumulator of
@@ -158,6 +165,119 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
     }
 }
 
+// ---- the mask-free step, cut into phases whose LDS operands are fetched one phase ahead ----
+// An LDS read takes a few hundred cycles to return while an MFMA issues every 32; left to itself
+// the compiler puts each read right in front of the MFMA that consumes it and the matrix pipe
+// waits most of the time.  Here every phase first ISSUES the reads of the next phase into a second
+// set of registers and then runs its own MFMAs / vector work on operands that arrived long ago;
+// sched_barriers keep the phases apart.
+template <int D>
+struct DkdvOpsA {  // operands of S = Q K^T and dP = dO V^T for one 32-query half
+    bf16x8 q[BwdCfg<D>::KS], d[BwdCfg<D>::KS];
+};
+template <int D>
+struct DkdvOpsC {  // operands of dV^T += dO^T P and dK^T += Q^T dS for one half
+    bf16x8 o[2][BwdCfg<D>::DB], q[2][BwdCfg<D>::DB];
+};
+template <int D, int HALF>
+__device__ __forceinline__ void dkdv_load_A(const unsigned char* stage, const int (&aaddr)[BwdCfg<D>::KS],
+                                            DkdvOpsA<D>& f, f32x16& dp, int hh) {
+    using C = BwdCfg<D>;
+    constexpr int ROWB = C::T::ROWB;
+    const unsigned char* stat = stage + 2 * C::TILE;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+        f.q[ks] = *(const bf16x8*)(stage + aaddr[ks] + HALF * 32 * ROWB);
+        f.d[ks] = *(const bf16x8*)(stage + C::TILE + aaddr[ks] + HALF * 32 * ROWB);
+    }
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {  // dP accumulates on top of -Delta
+        const int qoff = 32 * HALF + 8 * r4 + 4 * hh;
+        const float4 d4 = *(const float4*)(stat + (qoff >> 4) * 128 + (qoff & 15) * 4 + 64);
+        dp[4 * r4 + 0] = d4.x; dp[4 * r4 + 1] = d4.y; dp[4 * r4 + 2] = d4.z; dp[4 * r4 + 3] = d4.w;
+    }
+}
+template <int D, int HALF>
+__device__ __forceinline__ void dkdv_load_lse(const unsigned char* stage, float (&lv)[16], int hh) {
+    const unsigned char* stat = stage + 2 * BwdCfg<D>::TILE;
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        const int qoff = 32 * HALF + 8 * r4 + 4 * hh;
+        const float4 l4 = *(const float4*)(stat + (qoff >> 4) * 128 + (qoff & 15) * 4);
+        lv[4 * r4 + 0] = l4.x; lv[4 * r4 + 1] = l4.y; lv[4 * r4 + 2] = l4.z; lv[4 * r4 + 3] = l4.w;
+    }
+}
+template <int D, int HALF>
+__device__ __forceinline__ void dkdv_load_C(const unsigned char* stage, const int (&taddr)[BwdCfg<D>::DB][2],
+                                            DkdvOpsC<D>& f) {
+    using C = BwdCfg<D>;
+    constexpr int ROWB = C::T::ROWB;
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        const unsigned char* qt = stage + (32 * HALF + 16 * st) * ROWB;
+        const unsigned char* dot = qt + C::TILE;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) {
+            f.o[st][db] = cat4(lds_read_tr(dot + taddr[db][0]), lds_read_tr(dot + taddr[db][1]));
+            f.q[st][db] = cat4(lds_read_tr(qt + taddr[db][0]), lds_read_tr(qt + taddr[db][1]));
+        }
+    }
+}
+template <int D>
+__device__ __forceinline__ void dkdv_run_A(const DkdvOpsA<D>& f, const bf16x8 (&kf)[BwdCfg<D>::KS],
+                                           const bf16x8 (&vf)[BwdCfg<D>::KS], f32x16& s, f32x16& dp) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < BwdCfg<D>::KS; ++ks) {
+        s = mfma32(f.q[ks], kf[ks], s);
+        dp = mfma32(f.d[ks], vf[ks], dp);
+    }
+}
+// P = exp2(S c2 - lse2) and dS = P (dP - Delta), rounded to bf16 (vector ALU only)
+__device__ __forceinline__ void dkdv_run_B(const f32x16& s, const f32x16& dp, const float (&lv)[16], float c2,
+                                           bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) {
+    f32x16 p, ds;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        p[r] = fast_exp2(__builtin_fmaf(s[r], c2, -lv[r]));
+        ds[r] = p[r] * dp[r];
+    }
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        pb[st] = pack_regs(p, st);
+        dsb[st] = pack_regs(ds, st);
+    }
+}
+template <int D>
+__device__ __forceinline__ void dkdv_run_C(const DkdvOpsC<D>& f, const bf16x8 (&pb)[2], const bf16x8 (&dsb)[2],
+                                           f32x16 (&dkacc)[BwdCfg<D>::DB], f32x16 (&dvacc)[BwdCfg<D>::DB]) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int db = 0; db < BwdCfg<D>::DB; ++db) {
+            dvacc[db] = mfma32(f.o[st][db], pb[st], dvacc[db]);
+            dkacc[db] = mfma32(f.q[st][db], dsb[st], dkacc[db]);
+        }
+}
+
+// Load K of the 2*NI + 1 direct-to-LDS loads of one dK/dV step: K = 0 the stats, then NI loads of the Q
+// tile, then NI of the dO tile.  K beyond that is a no-op, so callers can name slots freely.
+template <int D, int K>
+__device__ __forceinline__ void dkdv_issue_part(bool valid, bool ragged, const TileDma<D, 64>& dma,
+                                                const unsigned char* q, const unsigned char* dO,
+                                                const unsigned char* st, uint32_t stat_off, uint32_t lds,
+                                                int wave, int lane) {
+    constexpr int NI = BwdCfg<D>::NI;
+    if constexpr (K == 0) {
+        if (valid && lane < 32) dma4(st, stat_off, lds + 2 * BwdCfg<D>::TILE + wave * 128);
+    } else if constexpr (K <= NI) {
+        if (valid) dma.template issue_one<K - 1>(q, ragged, lds, wave);
+    } else if constexpr (K <= 2 * NI) {
+        if (valid) dma.template issue_one<K - 1 - NI>(dO, ragged, lds + BwdCfg<D>::TILE, wave);
+    }
+}
+
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
@@ -168,10 +288,12 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE + C::STAT_BYTES;  // Q tile, dO tile, stats
     constexpr int PER = 2 * C::NI + 1;                  // loads per wave per step
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[3 * STAGE];
+    constexpr int NST = 4;                              // LDS stages
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int item = blockIdx.x / Hkv;
     if (item >= hdr[0]) return;
+    stagger_wave_priority();
     const int c = blockIdx.x % Hkv;
     const int g = Hq / Hkv;
     const WorkItem it = items[item];
@@ -202,18 +324,40 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const uint32_t stat_last = (uint32_t)min(srow, L - 1 - last_q0) * 8 + ((l >> 4) & 1) * 4;
     int iss_h = 0, iss_s = 0, iss_stage = 0;
     const uint32_t lds0 = lds_address(lds);
-    auto issue_next = [&]() -> bool {  // wave-uniform
-        if (iss_h >= g) return false;
+    // The loads of one step are either issued in one go (prologue, careful steps) or, in the main
+    // loop, one instruction per compute phase: begin_issue() fixes the step, issue_part<K>() emits
+    // load K of its PER loads (K = 0: stats, then NI for Q, then NI for dO).
+    bool iss_valid = false, iss_ragged = false;
+    const unsigned char *iss_q = nullptr, *iss_do = nullptr, *iss_st = nullptr;
+    uint32_t iss_lds = 0;
+    auto begin_issue = [&]() {  // wave-uniform
+        iss_valid = iss_h < g;
+        if (!iss_valid) return;
         const int h = c * g + iss_h;
         const int q0 = (first + iss_s) * BWD_STEP_Q;
-        const uint32_t stage = lds0 + iss_stage * STAGE;
-        const unsigned char* sbase = (const unsigned char*)(stats + (size_t)h * T + sb + q0);
-        if (l < 32) dma4(sbase, q0 + BWD_STEP_Q > L ? stat_last : stat_full, stage + 2 * C::TILE + w * 128);
-        dma.issue((const unsigned char*)(Q + ((size_t)sb * Hq + h) * D), q_row_bytes, q0, L, stage, w);
-        dma.issue((const unsigned char*)(dO + ((size_t)sb * Hq + h) * D), q_row_bytes, q0, L, stage + C::TILE, w);
+        iss_lds = lds0 + iss_stage * STAGE;
+        iss_ragged = q0 + BWD_STEP_Q > L;
+        iss_st = (const unsigned char*)(stats + (size_t)h * T + sb + q0);
+        iss_q = (const unsigned char*)(Q + ((size_t)(sb + q0) * Hq + h) * D);
+        iss_do = (const unsigned char*)(dO + ((size_t)(sb + q0) * Hq + h) * D);
         if (++iss_s == nsteps) { iss_s = 0; ++iss_h; }
-        iss_stage = iss_stage == 2 ? 0 : iss_stage + 1;
-        return true;
+        iss_stage = iss_stage == NST - 1 ? 0 : iss_stage + 1;
+    };
+    auto issue_stat = [&]() {
+        if (iss_valid && l < 32) dma4(iss_st, iss_ragged ? stat_last : stat_full, iss_lds + 2 * C::TILE + w * 128);
+    };
+    // slot S of 6 per step carries loads S and S + 6
+#define VA_DKDV_ISSUE_SLOT(S)                                                                                  \
+    dkdv_issue_part<D, (S)>(iss_valid, iss_ragged, dma, iss_q, iss_do, iss_st, iss_ragged ? stat_last : stat_full, \
+                            iss_lds, w, l);                                                                    \
+    dkdv_issue_part<D, (S) + 6>(iss_valid, iss_ragged, dma, iss_q, iss_do, iss_st, 0, iss_lds, w, l);
+    auto issue_all = [&]() {
+        begin_issue();
+        issue_stat();
+        if (iss_valid) {
+            dma.issue(iss_q, q_row_bytes, 0, iss_ragged ? 0 : BWD_STEP_Q, iss_lds, w);
+            dma.issue(iss_do, q_row_bytes, 0, iss_ragged ? 0 : BWD_STEP_Q, iss_lds + C::TILE, w);
+        }
     };
 
     int aaddr[C::KS], taddr[C::DB][2];
@@ -225,10 +369,11 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         taddr[db][1] = LT::tr_off(l, 8, db);
     }
 
-    // prologue: two steps in flight plus this lane's K and V fragments; all waited for once (see the
+    // prologue: three steps in flight plus this lane's K and V fragments; all waited for once (see the
     // forward kernel for why the register loads must not be left pending at loop entry)
-    issue_next();
-    issue_next();
+    issue_all();
+    issue_all();
+    issue_all();
     bf16x8 kf[C::KS], vf[C::KS];
     {
         const size_t off = ((size_t)(sb + (kvalid ? kv : 0)) * Hkv + c) * D + 8 * hh;
@@ -249,44 +394,107 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
     const float c2 = scale * kLog2e;
     const int wk_lo = kv0 + 32 * w;
+    const int total = g * nsteps;
 
-    int stage_i = 0;
-#define VA_DKDV_BEGIN()                                                              \
-        const bool issued = issue_next(); /* step idx + 2 */                             \
-        const unsigned char* b = lds + stage_i * STAGE;                                  \
-        const int q0 = (first + st) * BWD_STEP_Q;
-#define VA_DKDV_END()                                                                \
-        if (issued) wait_vmcnt<PER>(); else wait_vmcnt<0>(); /* step idx + 1 landed */   \
+    // Stage protocol.  Step i lives in stage i % 4.  VA_DKDV_SYNC() ends the part of step idx that
+    // reads stage idx - 1: it waits until step idx + 1 has landed (step idx + 2, issued one sync
+    // earlier, may stay in flight), passes the barrier, after which every wave is done with stage
+    // idx - 1, and refills that stage with step idx + 3.
+    int idx = 0, stage_i = 0;
+#ifdef VA_PHASE_CLOCKS
+    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter(), tstart = tprev;
+#endif
+#define VA_DKDV_SYNC()                                                               \
+        if (idx + 2 < total) wait_vmcnt<PER>(); else wait_vmcnt<0>();                    \
+        VA_CLK(4)                                                                        \
         wg_barrier();                                                                    \
-        stage_i = stage_i == 2 ? 0 : stage_i + 1;
-#define VA_DKDV_CAREFUL()                                                            \
+        VA_CLK(5)
+#define VA_DKDV_ADVANCE()                                                            \
+        ++idx;                                                                           \
+        stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
+#define VA_DKDV_CAREFUL(st)                                                          \
+    {                                                                                    \
+        const unsigned char* b = lds + stage_i * STAGE;                                  \
+        const int q0 = (first + (st)) * BWD_STEP_Q;                                      \
         /* causal: a query step entirely above this wave's keys sees none of them; every other  \
            step here takes the masked variant (a superset of the plain one) to keep code small */ \
         if (!CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo)                                     \
             dkdv_step<D, CAUSAL, true>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
-                                       c2, q0, kv, L, hh);
+                                       c2, q0, kv, L, hh);                               \
+        VA_DKDV_SYNC()                                                                   \
+        issue_all();                                                                     \
+        VA_DKDV_ADVANCE()                                                                \
+    }
 
     for (int hg = 0; hg < g; ++hg) {
         int st = 0;
-        for (; st < n_head; ++st) {
-            VA_DKDV_BEGIN()
-            VA_DKDV_CAREFUL()
-            VA_DKDV_END()
+        for (; st < n_head; ++st) VA_DKDV_CAREFUL(st)
+        if (st < n_tail) {
+            // Mask-free steps.  Per half: phase A (S, dP MFMAs), phase B (vector ALU), phase C (dV, dK
+            // MFMAs); each phase also issues the LDS reads of the phase after it.  The step's sync
+            // sits at its start: it only has to retire stage idx - 1, and having stage idx + 1
+            // published early lets the last phase fetch the next step's first operands.
+            DkdvOpsA<D> fa;
+            DkdvOpsC<D> fc;
+            f32x16 s, dpa, dpb;  // dP accumulators of the even / odd half, preloaded with -Delta
+            float lv[16];
+            bf16x8 pb[2], dsb[2];
+            dkdv_load_A<D, 0>(lds + stage_i * STAGE, aaddr, fa, dpa, hh);
+            for (; st < n_tail; ++st) {
+                VA_CLK(6)
+                VA_DKDV_SYNC()
+                begin_issue();
+                VA_CLK(0)
+                const unsigned char* cur = lds + stage_i * STAGE;
+                const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
+                // half 0
+                dkdv_load_C<D, 0>(cur, taddr, fc);
+                dkdv_load_lse<D, 0>(cur, lv, hh);
+                dkdv_run_A<D>(fa, kf, vf, s, dpa);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(0)
+                VA_CLK(1)
+                dkdv_load_A<D, 1>(cur, aaddr, fa, dpb, hh);
+                dkdv_run_B(s, dpa, lv, c2, pb, dsb);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(1)
+                VA_CLK(2)
+                dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(2)
+                VA_CLK(3)
+                // half 1
+                dkdv_load_C<D, 1>(cur, taddr, fc);
+                dkdv_load_lse<D, 1>(cur, lv, hh);
+                dkdv_run_A<D>(fa, kf, vf, s, dpb);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(3)
+                VA_CLK(1)
+                dkdv_load_A<D, 0>(nxt, aaddr, fa, dpa, hh);  // next step (dropped after the last one)
+                dkdv_run_B(s, dpb, lv, c2, pb, dsb);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(4)
+                VA_CLK(2)
+                dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+                __builtin_amdgcn_sched_barrier(0);
+                VA_DKDV_ISSUE_SLOT(5)
+                VA_CLK(3)
+                VA_DKDV_ADVANCE()
+            }
         }
-        for (; st < n_tail; ++st) {  // mask-free, every wave active: nothing conditional around the step
-            VA_DKDV_BEGIN()
-            dkdv_step<D, CAUSAL, false>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, c2,
-                                        q0, kv, L, hh);
-            VA_DKDV_END()
-        }
-        for (; st < nsteps; ++st) {
-            VA_DKDV_BEGIN()
-            VA_DKDV_CAREFUL()
-            VA_DKDV_END()
-        }
+        for (; st < nsteps; ++st) VA_DKDV_CAREFUL(st)
     }
-#undef VA_DKDV_BEGIN
-#undef VA_DKDV_END
+#ifdef VA_PHASE_CLOCKS
+    if (tid == 0) {
+        for (int i = 0; i < 7; ++i) atomicAdd(&g_phase[i], (unsigned long long)clk[i]);
+        atomicAdd(&g_phase[7], (unsigned long long)(__builtin_readcyclecounter() - tstart));
+        atomicAdd(&g_phase[8], 1ull);
+        atomicAdd(&g_phase[9], (unsigned long long)total);
+    }
+#endif
+#undef VA_DKDV_SYNC
+#undef VA_DKDV_ISSUE_SLOT
+#undef VA_DKDV_ADVANCE
 #undef VA_DKDV_CAREFUL
 
     if (kvalid) {
@@ -538,5 +746,12 @@ hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream) {
         default: return hipErrorInvalidValue;
     }
 }
+
+#ifdef VA_PHASE_CLOCKS
+extern "C" int varlen_attn_debug_phase(unsigned long long* out, int reset) {
+    if (reset) { unsigned long long z[16] = {}; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z)); }
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase), 16 * sizeof(unsigned long long));
+}
+#endif
 
 }  // namespace va

@@ -117,6 +117,17 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, uint32
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(VA_LDS const unsigned char*)p;
 }
+// Gives the waves that share a SIMD different, fixed issue priorities (by the parity of their
+// hardware wave slot).  Workgroups of equal work start together and, with equal priority, stay in
+// lock-step: both waves of a SIMD want the matrix pipe at the same time, then the vector ALU at the
+// same time, and each pipe idles while the other is fought over (measured: MFMA-busy + VALU-busy
+// = 100 %, co-execution < 20 %).  With unequal priorities one wave runs unhindered and the other
+// fills the gaps, so its MFMAs run under the first one's vector work and vice versa.
+__device__ __forceinline__ void stagger_wave_priority() {
+    const unsigned slot = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4);  // HW_ID[3:0]: wave slot in the SIMD
+    if (slot & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+}
+
 // Index of this wave inside its workgroup, as a value the compiler knows to be wave-uniform.
 __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
@@ -157,6 +168,16 @@ struct TileDma {
             if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
         }
     }
+    // One of the NI load instructions of a tile: src = first byte of the tile's first row at this
+    // head.  Lets a caller spread a tile's loads over its compute phases: a wave that issues them
+    // back to back right after a barrier queues up behind every other wave doing the same and sits
+    // in the issue stage for hundreds of cycles.
+    template <int I>
+    __device__ __forceinline__ void issue_one(const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
+        static_assert(I >= 0 && I < NI, "no such load");
+        const uint32_t off = ragged ? last[I] : full[I];
+        if (active[I]) dma16(src, off, tile + (wave * NI + I) * 1024);
+    }
 };
 
 // Wait until at most N of this wave's vector-memory loads (direct-to-LDS ones included) are still
@@ -170,9 +191,33 @@ __device__ __forceinline__ void wait_vmcnt() {
 // outstanding load, including the prefetches that are meant to stay in flight).
 __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
+    // this wave's own LDS reads must have returned before another wave may refill the tile
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), vmcnt and expcnt untouched
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
+
+// Asks the instruction scheduler to lay out the current straight-line region as N_MFMA rounds of
+// {2 LDS reads, 1 MFMA, 5 vector-ALU instructions}.  Used where a region holds matrix work and
+// vector work that do not depend on each other (software-pipelined loops): left alone the
+// scheduler emits them as two blocks and the wave leaves one pipe idle at a time.
+template <int N_MFMA, int DS_AHEAD = 10, int DS_PER = 2, int VALU_PER = 5>
+__device__ __forceinline__ void interleave_mfma_valu() {
+    // LDS reads run DS_AHEAD instructions ahead of the MFMAs that consume them: an LDS read takes a
+    // few hundred cycles to return, an MFMA issues every 32
+    __builtin_amdgcn_sched_group_barrier(0x100, DS_AHEAD, 0);
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);    // DS read
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);  // VALU
+    }
+}
+
+// Forces x to be computed by this point of the program: without it the compiler sinks a value's
+// whole computation into the later block that first uses it, i.e. out of the pipeline slot that was
+// meant to overlap it with matrix work.
+__device__ __forceinline__ void pin_here(bf16x8& x) { asm volatile("" : "+v"(x)); }
 
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7) {
     bf16x8 r;
