@@ -60,6 +60,60 @@ def cpu_baseline(w, budget_flops=8e11):
                       f"{flops:.3e} useful flop) of the same batch, all heads, {dt:.1f} s"}
 
 
+def report(args, torch, binding, W, to_gpu_bf16):
+    """Per-config table: median duration of the whole forward call and of the whole backward call."""
+    cases = [("2", W.make(2, with_dout=True)), ("3", W.make(3, with_dout=True)), ("3-short", None),
+             ("4", W.make(4, with_dout=True)), ("5", W.make(5, with_dout=True))]
+    w3 = cases[1][1]
+    short = w3.lengths[w3.lengths < w3.lengths.max()]
+    cases[2] = ("3-short", W.make_custom(short, w3.num_q_heads, w3.num_kv_heads, w3.head_dim, w3.causal,
+                                         seed=w3.seed, with_dout=True, scale=w3.scale))
+    print("| config | mask | B | T | Hq/Hkv | D | pass | median ms | useful TFLOP/s | % of 2.5 PFLOP/s "
+          "| min HBM GB | GB/s at min bytes |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|", flush=True)
+    for name, w in cases:
+        q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
+        cu = torch.from_numpy(w.cu_seqlens).cuda()
+        T = w.total_tokens
+        p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale)
+        o = torch.empty_like(q)
+        lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
+        ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+        def fwd():
+            binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f)
+
+        def bwd():
+            binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
+                                    workspace=ws_b)
+
+        e = 2 * w.head_dim * T
+        qo, kv = e * w.num_q_heads, e * w.num_kv_heads
+        stat = 4 * T * w.num_q_heads
+        # forward: read Q, K, V, write O, LSE; backward: read Q, K, V, O, dO, LSE, write dQ, dK, dV
+        min_bytes = {"fwd": 2 * qo + 2 * kv + stat, "bwd": 4 * qo + 4 * kv + stat}
+        for pname, fn, flops in (("fwd", fwd, w.fwd_flops()), ("bwd", bwd, w.bwd_flops())):
+            for _ in range(args.warmup):
+                fn()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(args.steps)]
+            for a, b in ev:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+            tf = flops / (ms * 1e-3) / 1e12
+            print(f"| {name} | {'causal' if w.causal else 'full'} | {w.num_seqs} | {T} | "
+                  f"{w.num_q_heads}/{w.num_kv_heads} | {w.head_dim} | {pname} | {ms:.3f} | {tf:.1f} | "
+                  f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {min_bytes[pname] / 1e9:.3f} | "
+                  f"{min_bytes[pname] / (ms * 1e-3) / 1e9:.0f} |", flush=True)
+        del q, k, v, do, o, lse, ws_f, ws_b, dq, dk, dv
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +121,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5],
                     help="5 (default): ViT batch forward+backward; 2, 3, 4: forward only on that config")
+    ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=None,
+                    help="override what a step is (default: fwd+bwd for config 5, fwd otherwise)")
+    ap.add_argument("--report", action="store_true",
+                    help="instead of the one JSON line: time forward and backward separately on configs "
+                         "2, 3, 3 without its long sample, 4 and 5 (median over --steps calls, HIP events "
+                         "around the whole library call) and print a markdown table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
@@ -84,8 +144,11 @@ def main():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(1)
     binding.load()
+    if args.report:
+        report(args, torch, binding, W, to_gpu_bf16)
+        return
 
-    with_bwd = args.config == 5
+    with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5
     w = W.make(args.config, with_dout=True)
     q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
     cu = torch.from_numpy(w.cu_seqlens).cuda()
