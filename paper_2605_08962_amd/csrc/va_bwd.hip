@@ -264,17 +264,16 @@ __device__ __forceinline__ void dkdv_run_C(const DkdvOpsC<D>& f, const bf16x8 (&
 // Load K of the 2*NI + 1 direct-to-LDS loads of one dK/dV step: K = 0 the stats, then NI loads of the Q
 // tile, then NI of the dO tile.  K beyond that is a no-op, so callers can name slots freely.
 template <int D, int K>
-__device__ __forceinline__ void dkdv_issue_part(bool valid, bool ragged, const TileDma<D, 64>& dma,
-                                                const unsigned char* q, const unsigned char* dO,
-                                                const unsigned char* st, uint32_t stat_off, uint32_t lds,
-                                                int wave, int lane) {
+__device__ __forceinline__ void dkdv_issue_part(bool ragged, const TileDma<D, 64>& dma, const unsigned char* q,
+                                                const unsigned char* dO, const unsigned char* st,
+                                                uint32_t stat_off, uint32_t lds, int wave) {
     constexpr int NI = BwdCfg<D>::NI;
     if constexpr (K == 0) {
-        if (valid && lane < 32) dma4(st, stat_off, lds + 2 * BwdCfg<D>::TILE + wave * 128);
+        dma4(st, stat_off, lds + 2 * BwdCfg<D>::TILE + (wave & 1) * 256);
     } else if constexpr (K <= NI) {
-        if (valid) dma.template issue_one<K - 1>(q, ragged, lds, wave);
+        dma.template issue_one<K - 1>(q, ragged, lds, wave);
     } else if constexpr (K <= 2 * NI) {
-        if (valid) dma.template issue_one<K - 1 - NI>(dO, ragged, lds + BwdCfg<D>::TILE, wave);
+        dma.template issue_one<K - 1 - NI>(dO, ragged, lds + BwdCfg<D>::TILE, wave);
     }
 }
 
@@ -313,51 +312,60 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const int n_head = (L < BWD_STEP_Q) ? nsteps : (CAUSAL ? min(2, nsteps) : 0);
     const int n_tail = max(n_head, nsteps - ((L % BWD_STEP_Q) ? 1 : 0));
 
-    // staging state: the next (head, step) to issue
+    // Staging state: pointers to the next (head, step) to issue, advanced by additions only.  Every
+    // quantity here is wave-uniform (scalar registers).  Loads are issued unconditionally: once the
+    // last step has been issued the state stops advancing and later calls fetch that step again into
+    // a stage nobody will read, so that the loop needs no branches around its loads and the count of
+    // outstanding loads per step is the same everywhere.
     const uint32_t q_row_bytes = (uint32_t)Hq * D * 2;
     TileDma<D, 64> dma;  // Q and dO share the offsets
     dma.init(q_row_bytes, L, w, l);
-    // stats: lanes 0..15 fetch lse2, lanes 16..31 delta, of rows 16*w + (lane & 15) of the step
-    const int srow = 16 * w + (l & 15);
+    // stats: a wave fetches {lse2, -Delta} of 32 rows (waves w and w + 2 fetch the same ones): lanes
+    // [0,16) lse2 and [16,32) -Delta of the first 16 rows, lanes [32,64) the same of the next 16
+    const int srow = 32 * (w & 1) + 16 * (l >> 5) + (l & 15);
     const int last_q0 = (L - 1) / BWD_STEP_Q * BWD_STEP_Q;
     const uint32_t stat_full = (uint32_t)srow * 8 + ((l >> 4) & 1) * 4;
     const uint32_t stat_last = (uint32_t)min(srow, L - 1 - last_q0) * 8 + ((l >> 4) & 1) * 4;
-    int iss_h = 0, iss_s = 0, iss_stage = 0;
     const uint32_t lds0 = lds_address(lds);
-    // The loads of one step are either issued in one go (prologue, careful steps) or, in the main
-    // loop, one instruction per compute phase: begin_issue() fixes the step, issue_part<K>() emits
-    // load K of its PER loads (K = 0: stats, then NI for Q, then NI for dO).
-    bool iss_valid = false, iss_ragged = false;
+    const int total = g * nsteps;
+    const bool ragged_sample = (L % BWD_STEP_Q) != 0;
+    const int64_t step_q = (int64_t)BWD_STEP_Q * q_row_bytes, step_st = (int64_t)BWD_STEP_Q * 8;
+    const int64_t wrap_q = (int64_t)D * 2 - (int64_t)(nsteps - 1) * step_q;       // last step of a head -> first of the next
+    const int64_t wrap_st = (int64_t)T * 8 - (int64_t)(nsteps - 1) * step_st;
+    const size_t qoff0 = ((size_t)(sb + first * BWD_STEP_Q) * Hq + (size_t)c * g) * D * 2;
+    const unsigned char* nxt_q = (const unsigned char*)Q + qoff0;
+    const unsigned char* nxt_do = (const unsigned char*)dO + qoff0;
+    const unsigned char* nxt_st = (const unsigned char*)(stats + (size_t)c * g * T + sb + first * BWD_STEP_Q);
+    int nxt_s = 0, nxt_n = 0, iss_stage = 0;
+    // the step the current round of loads belongs to (set by begin_issue)
+    bool iss_ragged = false;
     const unsigned char *iss_q = nullptr, *iss_do = nullptr, *iss_st = nullptr;
     uint32_t iss_lds = 0;
-    auto begin_issue = [&]() {  // wave-uniform
-        iss_valid = iss_h < g;
-        if (!iss_valid) return;
-        const int h = c * g + iss_h;
-        const int q0 = (first + iss_s) * BWD_STEP_Q;
+    auto begin_issue = [&]() {
+        iss_q = nxt_q; iss_do = nxt_do; iss_st = nxt_st;
+        iss_ragged = ragged_sample && nxt_s == nsteps - 1;
         iss_lds = lds0 + iss_stage * STAGE;
-        iss_ragged = q0 + BWD_STEP_Q > L;
-        iss_st = (const unsigned char*)(stats + (size_t)h * T + sb + q0);
-        iss_q = (const unsigned char*)(Q + ((size_t)(sb + q0) * Hq + h) * D);
-        iss_do = (const unsigned char*)(dO + ((size_t)(sb + q0) * Hq + h) * D);
-        if (++iss_s == nsteps) { iss_s = 0; ++iss_h; }
         iss_stage = iss_stage == NST - 1 ? 0 : iss_stage + 1;
+        const bool more = nxt_n + 1 < total;
+        const bool wrap = nxt_s == nsteps - 1;
+        const int64_t aq = more ? (wrap ? wrap_q : step_q) : 0, as = more ? (wrap ? wrap_st : step_st) : 0;
+        nxt_q += aq; nxt_do += aq; nxt_st += as;
+        nxt_s = more ? (wrap ? 0 : nxt_s + 1) : nxt_s;
+        nxt_n += more ? 1 : 0;
     };
     auto issue_stat = [&]() {
-        if (iss_valid && l < 32) dma4(iss_st, iss_ragged ? stat_last : stat_full, iss_lds + 2 * C::TILE + w * 128);
+        dma4(iss_st, iss_ragged ? stat_last : stat_full, iss_lds + 2 * C::TILE + (w & 1) * 256);
     };
     // slot S of 6 per step carries loads S and S + 6
-#define VA_DKDV_ISSUE_SLOT(S)                                                                                  \
-    dkdv_issue_part<D, (S)>(iss_valid, iss_ragged, dma, iss_q, iss_do, iss_st, iss_ragged ? stat_last : stat_full, \
-                            iss_lds, w, l);                                                                    \
-    dkdv_issue_part<D, (S) + 6>(iss_valid, iss_ragged, dma, iss_q, iss_do, iss_st, 0, iss_lds, w, l);
+#define VA_DKDV_ISSUE_SLOT(S)                                                                             \
+    dkdv_issue_part<D, (S)>(iss_ragged, dma, iss_q, iss_do, iss_st, iss_ragged ? stat_last : stat_full,   \
+                            iss_lds, w);                                                                  \
+    dkdv_issue_part<D, (S) + 6>(iss_ragged, dma, iss_q, iss_do, iss_st, 0, iss_lds, w);
     auto issue_all = [&]() {
         begin_issue();
         issue_stat();
-        if (iss_valid) {
-            dma.issue(iss_q, q_row_bytes, 0, iss_ragged ? 0 : BWD_STEP_Q, iss_lds, w);
-            dma.issue(iss_do, q_row_bytes, 0, iss_ragged ? 0 : BWD_STEP_Q, iss_lds + C::TILE, w);
-        }
+        dma.issue_tile(iss_q, iss_ragged, iss_lds, w);
+        dma.issue_tile(iss_do, iss_ragged, iss_lds + C::TILE, w);
     };
 
     int aaddr[C::KS], taddr[C::DB][2];
@@ -394,7 +402,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
     const float c2 = scale * kLog2e;
     const int wk_lo = kv0 + 32 * w;
-    const int total = g * nsteps;
 
     // Stage protocol.  Step i lives in stage i % 4.  VA_DKDV_SYNC() ends the part of step idx that
     // reads stage idx - 1: it waits until step idx + 1 has landed (step idx + 2, issued one sync
@@ -405,7 +412,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter(), tstart = tprev;
 #endif
 #define VA_DKDV_SYNC()                                                               \
-        if (idx + 2 < total) wait_vmcnt<PER>(); else wait_vmcnt<0>();                    \
+        wait_vmcnt<PER>();                                                               \
         VA_CLK(4)                                                                        \
         wg_barrier();                                                                    \
         VA_CLK(5)
@@ -443,14 +450,14 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
             for (; st < n_tail; ++st) {
                 VA_CLK(6)
                 VA_DKDV_SYNC()
-                begin_issue();
                 VA_CLK(0)
                 const unsigned char* cur = lds + stage_i * STAGE;
                 const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
-                // half 0
+                // half 0 (the scalar bookkeeping of this step's loads runs behind its MFMAs)
                 dkdv_load_C<D, 0>(cur, taddr, fc);
                 dkdv_load_lse<D, 0>(cur, lv, hh);
                 dkdv_run_A<D>(fa, kf, vf, s, dpa);
+                begin_issue();
                 __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(0)
                 VA_CLK(1)
@@ -492,6 +499,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         atomicAdd(&g_phase[9], (unsigned long long)total);
     }
 #endif
+    wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
 #undef VA_DKDV_SYNC
 #undef VA_DKDV_ISSUE_SLOT
 #undef VA_DKDV_ADVANCE

@@ -168,6 +168,14 @@ struct TileDma {
             if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
         }
     }
+    // All loads of a tile whose first row's bytes at this head start at src.
+    __device__ __forceinline__ void issue_tile(const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const uint32_t off = ragged ? last[i] : full[i];
+            if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+        }
+    }
     // One of the NI load instructions of a tile: src = first byte of the tile's first row at this
     // head.  Lets a caller spread a tile's loads over its compute phases: a wave that issues them
     // back to back right after a barrier queues up behind every other wave doing the same and sits
