@@ -21,9 +21,13 @@ namespace va {
 
 #ifdef VA_PHASE_CLOCKS
 __device__ unsigned long long g_phase[16];
-#define VA_CLK(i) { long long t_ = __builtin_readcyclecounter(); clk[i] += t_ - tprev; tprev = t_; }
+// Time stamps are only taken (scalar memory clock reads) where VA_CLK stands and are consumed by
+// VA_CLK_ACCUM once per step, so that waiting for them does not serialise the phases they separate.
+#define VA_CLK(i) tm[i] = __builtin_readcyclecounter();
+#define VA_CLK_ACCUM(n) { _Pragma("unroll") for (int i_ = 0; i_ < (n); ++i_) clk[i_] += tm[i_ + 1] - tm[i_]; }
 #else
 #define VA_CLK(i)
+#define VA_CLK_ACCUM(n)
 #endif
 
 // ------------------------------------------------------------------------------------------------
@@ -261,6 +265,34 @@ __device__ __forceinline__ void dkdv_run_C(const DkdvOpsC<D>& f, const bf16x8 (&
         }
 }
 
+// The same work cut differently: S alone, then dP, dV and dK with the vector work in their shadow.
+// A wave that has just issued an MFMA cannot issue anything for about 16 cycles and is then free for
+// about 16 more before the matrix pipe takes the next one (measured: up to 3 vector instructions per
+// MFMA cost nothing, further ones about 4.5 cycles each).  Vector work that does not depend on the
+// MFMAs around it is therefore cheapest when spread between them.
+template <int D>
+__device__ __forceinline__ void dkdv_run_S(const DkdvOpsA<D>& f, const bf16x8 (&kf)[BwdCfg<D>::KS], f32x16& s) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < BwdCfg<D>::KS; ++ks) s = mfma32(f.q[ks], kf[ks], s);
+}
+template <int D>
+__device__ __forceinline__ void dkdv_run_dP(const DkdvOpsA<D>& f, const bf16x8 (&vf)[BwdCfg<D>::KS], f32x16& dp) {
+#pragma unroll
+    for (int ks = 0; ks < BwdCfg<D>::KS; ++ks) dp = mfma32(f.d[ks], vf[ks], dp);
+}
+// rounds of {1 MFMA, DS_PER LDS reads, VALU_PER vector instructions} for the region that ends here
+template <int N_MFMA, int DS_PER, int VALU_PER>
+__device__ __forceinline__ void dkdv_interleave() {
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (DS_PER) __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);
+    }
+}
+
 // Load K of the 2*NI + 1 direct-to-LDS loads of one dK/dV step: K = 0 the stats, then NI loads of the Q
 // tile, then NI of the dO tile.  K beyond that is a no-op, so callers can name slots freely.
 template <int D, int K>
@@ -409,13 +441,15 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     // idx - 1, and refills that stage with step idx + 3.
     int idx = 0, stage_i = 0;
 #ifdef VA_PHASE_CLOCKS
-    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter(), tstart = tprev;
+    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tm[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const long long tstart = __builtin_readcyclecounter();
+    unsigned long long nplain = 0;
 #endif
 #define VA_DKDV_SYNC()                                                               \
         wait_vmcnt<PER>();                                                               \
-        VA_CLK(4)                                                                        \
+        VA_CLK(1)                                                                        \
         wg_barrier();                                                                    \
-        VA_CLK(5)
+        VA_CLK(2)
 #define VA_DKDV_ADVANCE()                                                            \
         ++idx;                                                                           \
         stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
@@ -448,44 +482,49 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
             bf16x8 pb[2], dsb[2];
             dkdv_load_A<D, 0>(lds + stage_i * STAGE, aaddr, fa, dpa, hh);
             for (; st < n_tail; ++st) {
-                VA_CLK(6)
-                VA_DKDV_SYNC()
                 VA_CLK(0)
+                VA_DKDV_SYNC()
                 const unsigned char* cur = lds + stage_i * STAGE;
                 const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
                 // half 0 (the scalar bookkeeping of this step's loads runs behind its MFMAs)
-                dkdv_load_C<D, 0>(cur, taddr, fc);
                 dkdv_load_lse<D, 0>(cur, lv, hh);
-                dkdv_run_A<D>(fa, kf, vf, s, dpa);
+                dkdv_run_S<D>(fa, kf, s);
                 begin_issue();
                 __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(0)
-                VA_CLK(1)
-                dkdv_load_A<D, 1>(cur, aaddr, fa, dpb, hh);
-                dkdv_run_B(s, dpa, lv, c2, pb, dsb);
-                __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(1)
-                VA_CLK(2)
+                VA_CLK(3)
+                dkdv_load_C<D, 0>(cur, taddr, fc);
+                dkdv_run_dP<D>(fa, vf, dpa);
+                dkdv_run_B(s, dpa, lv, c2, pb, dsb);
                 dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+                dkdv_load_A<D, 1>(cur, aaddr, fa, dpb, hh);
+                dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
+                dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
                 __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(2)
-                VA_CLK(3)
+                VA_CLK(4)
                 // half 1
-                dkdv_load_C<D, 1>(cur, taddr, fc);
                 dkdv_load_lse<D, 1>(cur, lv, hh);
-                dkdv_run_A<D>(fa, kf, vf, s, dpb);
+                dkdv_run_S<D>(fa, kf, s);
                 __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(3)
-                VA_CLK(1)
-                dkdv_load_A<D, 0>(nxt, aaddr, fa, dpa, hh);  // next step (dropped after the last one)
-                dkdv_run_B(s, dpb, lv, c2, pb, dsb);
-                __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(4)
-                VA_CLK(2)
+                VA_CLK(5)
+                dkdv_load_C<D, 1>(cur, taddr, fc);
+                dkdv_run_dP<D>(fa, vf, dpb);
+                dkdv_run_B(s, dpb, lv, c2, pb, dsb);
                 dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+                dkdv_load_A<D, 0>(nxt, aaddr, fa, dpa, hh);  // next step (dropped after the last one)
+                dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
+                dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
                 __builtin_amdgcn_sched_barrier(0);
                 VA_DKDV_ISSUE_SLOT(5)
-                VA_CLK(3)
+                VA_CLK(6)
+#ifdef VA_PHASE_CLOCKS
+                VA_CLK_ACCUM(6)
+                ++nplain;
+#endif
                 VA_DKDV_ADVANCE()
             }
         }
@@ -497,6 +536,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         atomicAdd(&g_phase[7], (unsigned long long)(__builtin_readcyclecounter() - tstart));
         atomicAdd(&g_phase[8], 1ull);
         atomicAdd(&g_phase[9], (unsigned long long)total);
+        atomicAdd(&g_phase[10], nplain);
     }
 #endif
     wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
