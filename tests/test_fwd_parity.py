@@ -57,6 +57,21 @@ def test_peaky_softmax(D):
     _check_full(w, allow_output_rounding=True)
 
 
+@pytest.mark.parametrize("D,causal", [(64, False), (128, True), (80, False)])
+def test_scores_that_outgrow_the_first_tile(D, causal):
+    # The keys of each sample's first tile are tiny and the later ones large, so the reference
+    # maximum fixed by the first tile is exceeded by far more than 2^30 afterwards (scores reach
+    # several hundred): the mask-free tiles taken on trust must notice and repeat with a new maximum.
+    w = W.make_custom([500, 321, 64], 2, 2, D, causal, seed=77 + D)
+    k = W.bf16_bits_to_f32(w.k)
+    cu = w.cu_seqlens
+    for s in range(w.num_seqs):
+        k[cu[s]:cu[s] + 64] *= 0.01
+        k[cu[s] + 64:cu[s + 1]] *= 12.0
+    w.k = W.f32_to_bf16_bits(k)
+    _check_full(w, allow_output_rounding=True)
+
+
 def test_scale_zero_gives_prefix_means():
     from paper_2605_08962_amd import binding
     w = W.make_custom([70, 130], 2, 2, 64, True, seed=3)
