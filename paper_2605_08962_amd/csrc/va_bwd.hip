@@ -439,7 +439,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     // reads stage idx - 1: it waits until step idx + 1 has landed (step idx + 2, issued one sync
     // earlier, may stay in flight), passes the barrier, after which every wave is done with stage
     // idx - 1, and refills that stage with step idx + 3.
-    int idx = 0, stage_i = 0;
+    int stage_i = 0;  // stage of the current step ("idx" in the comment above)
 #ifdef VA_PHASE_CLOCKS
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tm[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     const long long tstart = __builtin_readcyclecounter();
@@ -451,7 +451,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         wg_barrier();                                                                    \
         VA_CLK(2)
 #define VA_DKDV_ADVANCE()                                                            \
-        ++idx;                                                                           \
         stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
 #define VA_DKDV_CAREFUL(st)                                                          \
     {                                                                                    \
