@@ -1,0 +1,92 @@
+"""Pins of the partitioner oracle (oracle/partition.py): worked textbook examples, brute force on
+tiny inputs, the known worst-case ratios, conservation and the equal-count property."""
+import itertools
+import random
+
+import pytest
+
+from oracle import partition as P
+
+
+def _sums(values, bin_of, bins):
+    return sorted(P.bin_costs(values, bin_of, bins, lin=1.0, quad=0.0))
+
+
+def test_two_way_differencing_worked_example():
+    # {8,7,6,5,4}: 8-7 -> 1, 6-5 -> 1, 4-1 -> 3, 3-1 -> 2: the two sets differ by 2 (16 and 14),
+    # although a perfect split {8,7} / {6,5,4} exists: the classic example of the method's gap
+    b = P.karmarkar_karp([8, 7, 6, 5, 4], 2, lin=1.0, quad=0.0)
+    assert _sums([8, 7, 6, 5, 4], b, 2) == [14.0, 16.0]
+
+
+def test_three_way_differencing_worked_example():
+    # by hand: (8,7,0) -> (8,7,6); (5,4,0); (5+6, 4+7, 0+8) = (11,11,8): bins {8}, {7,4}, {6,5}
+    vals = [8, 7, 6, 5, 4]
+    b = P.karmarkar_karp(vals, 3, lin=1.0, quad=0.0)
+    groups = sorted(sorted(v for v, bb in zip(vals, b) if bb == k) for k in range(3))
+    assert groups == [[4, 7], [5, 6], [8]]
+    assert b[0] == 2  # bins are numbered by decreasing cost: the lone 8 is the cheapest bin
+
+
+def test_lpt_worked_example():
+    # Graham's list scheduling on sorted jobs 7,7,6,6,5,5,4,4,4 with 4 machines... kept small:
+    # {5,5,4,4,3,3,3} on 3 bins: 5|5|4, 5|5|4+4, 5+3|5|8, 8|5+3|8, 8|8|8+3 -> 8, 8, 11
+    b = P.lpt([5, 5, 4, 4, 3, 3, 3], 3, lin=1.0, quad=0.0)
+    assert _sums([5, 5, 4, 4, 3, 3, 3], b, 3) == [8.0, 8.0, 11.0]
+    assert P.optimum_max_cost([5, 5, 4, 4, 3, 3, 3], 3, lin=1.0, quad=0.0) == 9.0  # {5,4},{5,4},{3,3,3}
+
+
+@pytest.mark.parametrize("bins", [2, 3, 4])
+def test_against_brute_force_and_worst_case_ratios(bins):
+    rng = random.Random(100 + bins)
+    for trial in range(60):
+        n = rng.randint(1, 9)
+        vals = [rng.randint(1, 40) for _ in range(n)]
+        opt = P.optimum_max_cost(vals, bins, lin=1.0, quad=0.0)
+        for method, bound in ((P.karmarkar_karp, 4.0 / 3.0), (P.lpt, 4.0 / 3.0 - 1.0 / (3.0 * bins))):
+            b = method(vals, bins, lin=1.0, quad=0.0)
+            assert len(b) == n and all(0 <= x < bins for x in b)
+            sums = P.bin_costs(vals, b, bins, lin=1.0, quad=0.0)
+            assert abs(sum(sums) - sum(vals)) < 1e-9          # every sample in exactly one bin
+            assert opt - 1e-9 <= max(sums) <= bound * opt + 1e-9, (method.__name__, vals, sums, opt)
+
+
+def test_quadratic_cost_is_what_gets_balanced():
+    # one long sample against many short ones: by token count 1 x 1000 = 10 x 100, by attention cost
+    # the long one alone outweighs all the short ones together
+    lengths = [1000] + [100] * 10
+    b = P.karmarkar_karp(lengths, 2, lin=0.0, quad=1.0)
+    assert [x for x in b[1:]] == [b[1]] * 10 and b[0] != b[1]
+    b = P.karmarkar_karp(lengths, 2, lin=1.0, quad=0.0)
+    assert _sums(lengths, b, 2) == [1000.0, 1000.0]
+
+
+@pytest.mark.parametrize("method", [P.karmarkar_karp, P.lpt])
+def test_equal_counts(method):
+    rng = random.Random(7)
+    for n, bins in ((16, 4), (17, 4), (5, 8), (64, 8)):
+        vals = [rng.randint(1, 1000) for _ in range(n)]
+        b = method(vals, bins, lin=1.0, quad=0.0, equal_counts=True)
+        counts = [b.count(k) for k in range(bins)]
+        assert max(counts) - min(counts) <= 1 and sum(counts) == n
+
+
+def test_result_does_not_depend_on_input_order_when_costs_are_distinct():
+    vals = [3, 17, 29, 41, 58, 66, 71, 89, 97, 104, 120]
+    ref = _sums(vals, P.karmarkar_karp(vals, 3, lin=1.0, quad=0.0), 3)
+    rng = random.Random(3)
+    for _ in range(10):
+        perm = vals[:]
+        rng.shuffle(perm)
+        assert _sums(perm, P.karmarkar_karp(perm, 3, lin=1.0, quad=0.0), 3) == ref
+
+
+def test_differencing_beats_or_matches_greedy_on_average():
+    # the reason the paper picks it: on random inputs its largest bin is (on average) smaller
+    rng = random.Random(11)
+    kk = lp = 0.0
+    for _ in range(200):
+        vals = [rng.randint(1, 10_000) for _ in range(24)]
+        kk += max(P.bin_costs(vals, P.karmarkar_karp(vals, 4, lin=1.0, quad=0.0), 4, lin=1.0, quad=0.0))
+        lp += max(P.bin_costs(vals, P.lpt(vals, 4, lin=1.0, quad=0.0), 4, lin=1.0, quad=0.0))
+    assert kk <= lp
