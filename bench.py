@@ -114,6 +114,56 @@ def report(args, torch, binding, W, to_gpu_bf16):
         torch.cuda.empty_cache()
 
 
+def balance(args, torch, binding, W, ranks=8):
+    """What the partitioner buys: time of the slowest rank's share over the mean share time."""
+    print("| batch | assignment | predicted max/mean (sum L^2) | measured max ms | mean ms | measured max/mean |")
+    print("|---|---|---|---|---|---|", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    for cfg in (2, 3):
+        w = W.make(cfg, lengths_only=True)
+        lengths = w.lengths.astype(np.int64)
+        n = lengths.size
+        assignments = {"as drawn (contiguous chunks)": np.arange(n) * ranks // n}
+        for name, method in (("greedy LPT", binding.PARTITION_LPT), ("Karmarkar-Karp", binding.PARTITION_KARMARKAR_KARP)):
+            assignments[name + ", any counts"] = binding.balance_partition(lengths, ranks, method)[0]
+            if n % ranks == 0:
+                assignments[name + f", {n // ranks} per rank"] = binding.balance_partition(
+                    lengths, ranks, method, equal_counts=True)[0]
+        for name, bin_of in assignments.items():
+            cost = np.bincount(bin_of, weights=lengths.astype(np.float64) ** 2, minlength=ranks)
+            times = []
+            for r in range(ranks):
+                Ls = lengths[bin_of == r]
+                if Ls.size == 0:
+                    times.append(0.0)
+                    continue
+                T = int(Ls.sum())
+                mk = lambda h: torch.randn((T, h, w.head_dim), device="cuda", dtype=torch.bfloat16, generator=gen)
+                q, k, v, do = mk(w.num_q_heads), mk(w.num_kv_heads), mk(w.num_kv_heads), mk(w.num_q_heads)
+                cu = torch.from_numpy(np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)).cuda()
+                o, lse = binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale)
+
+                def step():
+                    binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse)
+                    binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale)
+                step()
+                ev = []
+                for _ in range(max(3, args.steps // 4)):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    step()
+                    b.record()
+                    ev.append((a, b))
+                torch.cuda.synchronize()
+                times.append(float(np.median([a.elapsed_time(b) for a, b in ev])))
+                del q, k, v, do, o, lse
+            times = np.asarray(times)
+            print(f"| {w.name} ({n} samples, {ranks} ranks) | {name} | {cost.max() / cost.mean():.3f} | "
+                  f"{times.max():.3f} | {times.mean():.3f} | {times.max() / times.mean():.3f} |", flush=True)
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,6 +177,11 @@ def main():
                     help="instead of the one JSON line: time forward and backward separately on configs "
                          "2, 3, 3 without its long sample, 4 and 5 (median over --steps calls, HIP events "
                          "around the whole library call) and print a markdown table")
+    ap.add_argument("--balance", action="store_true",
+                    help="instead of the one JSON line: split the ViT batch's 64 images (and the long/short "
+                         "mix) over 8 ranks as drawn, by greedy LPT and by Karmarkar-Karp differencing "
+                         "(library's host-side partitioner, cost = L^2), run forward+backward on every "
+                         "rank's share on this GPU and print max / mean share time as a markdown table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
@@ -146,6 +201,9 @@ def main():
     binding.load()
     if args.report:
         report(args, torch, binding, W, to_gpu_bf16)
+        return
+    if args.balance:
+        balance(args, torch, binding, W)
         return
 
     with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5

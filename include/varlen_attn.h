@@ -108,6 +108,30 @@ int varlen_attn_last_hip_error(void);
 int64_t varlen_attn_max_work_items(const varlen_attn_params *p, int which);
 
 /*
+ * Length-balanced partition of a group's samples into `bins` subsets (one per rank): the step in
+ * front of the attention kernels in the paper's pipeline (Section 5.1, decentralized grouped
+ * reordering: after the sample sizes of a group of ranks are gathered, the samples are reordered
+ * "using the Karp algorithm").  The paper says no more; this is the k-way Karmarkar-Karp largest
+ * differencing method, or greedy longest-processing-time-first scheduling for comparison.
+ * HOST pointers only, no GPU work, thread-safe.
+ *   lengths      int32 [num_seqs], each >= 0
+ *   cost of a sample of length L = lin_cost * L + quad_cost * L * L   (both finite, >= 0;
+ *                  attention is the quadratic term)
+ *   equal_counts 1: bin sizes differ by at most one sample (fixed microbatch size per rank);
+ *                  0: any sizes
+ *   bin_of       int32 [num_seqs] (out): the bin of every sample; bin 0 is the most expensive
+ *                  one for the differencing method
+ *   bin_cost     double [bins] (out, may be NULL): summed cost per bin
+ * Ties: equal costs go to the lower sample index, equally cheap bins to the lower bin.
+ * Errors: VA_ERR_BAD_SHAPE (negative count or length, bins < 1, unknown method),
+ * VA_ERR_BAD_SCALE (cost coefficients), VA_ERR_NULL_PTR.  num_seqs == 0 returns VA_OK.
+ */
+enum { VA_PARTITION_KARMARKAR_KARP = 0, VA_PARTITION_LPT = 1 };
+int varlen_attn_balance_partition(const int32_t *lengths, int32_t num_seqs, int32_t bins, int32_t method,
+                                  int32_t equal_counts, double lin_cost, double quad_cost,
+                                  int32_t *bin_of, double *bin_cost);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled (process-wide), every kernel this library
  * launches is bracketed by two HIP events recorded on the caller's stream; launches are not
  * synchronised and results are unchanged.  Enabling drops earlier samples.  profile_read() waits

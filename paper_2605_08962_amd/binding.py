@@ -54,6 +54,9 @@ def load():
     lib.varlen_attn_status_string.restype = ctypes.c_char_p
     lib.varlen_attn_last_hip_error.argtypes = []
     lib.varlen_attn_last_hip_error.restype = ctypes.c_int
+    lib.varlen_attn_balance_partition.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_double, ctypes.c_double, vp, vp]
+    lib.varlen_attn_balance_partition.restype = ctypes.c_int
     lib.varlen_attn_profile_enable.argtypes = [ctypes.c_int]
     lib.varlen_attn_profile_enable.restype = ctypes.c_int
     lib.varlen_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -169,3 +172,21 @@ def profile_read():
         _check(load().varlen_attn_profile_read(kid, ctypes.byref(ms), ctypes.byref(n)))
         out[name] = (ms.value, n.value)
     return out
+
+
+PARTITION_KARMARKAR_KARP = 0
+PARTITION_LPT = 1
+
+
+def balance_partition(lengths, bins, method=PARTITION_KARMARKAR_KARP, equal_counts=False, lin_cost=0.0,
+                      quad_cost=1.0):
+    """Host-side: bin of every sample and the summed cost per bin (numpy arrays)."""
+    import numpy as np
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    bin_of = np.zeros(lengths.size, dtype=np.int32)
+    bin_cost = np.zeros(max(int(bins), 0), dtype=np.float64)
+    _check(load().varlen_attn_balance_partition(
+        lengths.ctypes.data_as(ctypes.c_void_p), lengths.size, int(bins), int(method), int(bool(equal_counts)),
+        float(lin_cost), float(quad_cost), bin_of.ctypes.data_as(ctypes.c_void_p),
+        bin_cost.ctypes.data_as(ctypes.c_void_p)))
+    return bin_of, bin_cost

@@ -1,5 +1,6 @@
 """Pins of the partitioner oracle (oracle/partition.py): worked textbook examples, brute force on
-tiny inputs, the known worst-case ratios, conservation and the equal-count property."""
+tiny inputs, the known worst-case ratios, conservation and the equal-count property; then the
+library's host-side partitioner against that oracle."""
 import itertools
 import random
 
@@ -90,3 +91,54 @@ def test_differencing_beats_or_matches_greedy_on_average():
         kk += max(P.bin_costs(vals, P.karmarkar_karp(vals, 4, lin=1.0, quad=0.0), 4, lin=1.0, quad=0.0))
         lp += max(P.bin_costs(vals, P.lpt(vals, 4, lin=1.0, quad=0.0), 4, lin=1.0, quad=0.0))
     assert kk <= lp
+
+
+# --- the library's host-side partitioner against the oracle (no GPU involved) ---
+
+def _groups(bin_of, bins):
+    return [sorted(i for i, b in enumerate(bin_of) if b == k) for k in range(bins)]
+
+
+@pytest.mark.parametrize("equal_counts", [False, True])
+@pytest.mark.parametrize("method", ["kk", "lpt"])
+def test_library_matches_oracle_exactly(method, equal_counts):
+    from paper_2605_08962_amd import binding, workloads as W
+    rng = random.Random(5)
+    cases = [[], [7], [5, 5, 5, 5], [8, 7, 6, 5, 4]]
+    cases += [[rng.randint(1, 9216) for _ in range(rng.randint(2, 70))] for _ in range(25)]
+    cases += [list(W.make(2, lengths_only=True).lengths), list(W.make(3, lengths_only=True).lengths),
+              list(W.make(4, lengths_only=True).lengths)]
+    for lengths in cases:
+        for bins in (1, 2, 3, 8):
+            for lin, quad in ((0.0, 1.0), (1.0, 0.0), (4096.0, 1.0)):
+                ref = (P.karmarkar_karp if method == "kk" else P.lpt)(lengths, bins, lin, quad, equal_counts)
+                got, cost = binding.balance_partition(
+                    lengths, bins, binding.PARTITION_KARMARKAR_KARP if method == "kk" else binding.PARTITION_LPT,
+                    equal_counts, lin, quad)
+                assert list(got) == ref, (lengths, bins, lin, quad)
+                assert list(cost) == P.bin_costs(lengths, ref, bins, lin, quad) or \
+                    max(abs(a - b) for a, b in zip(cost, P.bin_costs(lengths, ref, bins, lin, quad))) <= 1e-6 * max(cost)
+
+
+def test_library_partition_rejects_bad_arguments():
+    from paper_2605_08962_amd import binding
+    for kwargs in (dict(bins=0), dict(bins=2, method=5), dict(bins=2, quad_cost=-1.0), dict(bins=2, lin_cost=float("nan"))):
+        with pytest.raises(binding.VarlenAttnError):
+            binding.balance_partition([3, 4, 5], **kwargs)
+    with pytest.raises(binding.VarlenAttnError):
+        binding.balance_partition([3, -4, 5], 2)
+
+
+def test_library_partition_large_input_is_valid_and_balanced():
+    # 20000 samples in 64 bins: far beyond what the oracle's quadratic loops finish quickly; check
+    # what must hold at any size
+    import numpy as np
+    from paper_2605_08962_amd import binding
+    rng = np.random.default_rng(1)
+    lengths = np.floor(np.exp(rng.uniform(np.log(64), np.log(16384), 20000))).astype(np.int32)
+    c = lengths.astype(np.float64) ** 2
+    for method in (binding.PARTITION_KARMARKAR_KARP, binding.PARTITION_LPT):
+        b, cost = binding.balance_partition(lengths, 64, method)
+        assert b.min() >= 0 and b.max() < 64
+        assert np.allclose(np.bincount(b, weights=c, minlength=64), cost)
+        assert cost.max() / cost.mean() < 1.001
