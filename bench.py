@@ -164,6 +164,58 @@ def balance(args, torch, binding, W, ranks=8):
         torch.cuda.empty_cache()
 
 
+def lssp(args, torch, binding, W, ranks=8, model_heads=16):
+    """Section 4.1.1, long-short sequence parallelism, emulated on one GPU (no all-to-all): the time of
+    the attention layers of the slowest rank, as a function of the length threshold."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+    w = W.make(3, lengths_only=True)
+    rng = np.random.Generator(np.random.PCG64(2003))
+    mixes = {"long_short_mix_d80 (1 x 65536 + 256 x 64..1024)": w.lengths.astype(np.int64),
+             "log-uniform 256..32768, 96 samples": np.floor(np.exp(rng.uniform(np.log(256), np.log(32768), 96))).astype(np.int64)}
+
+    def run(Ls, heads):
+        if Ls.size == 0:
+            return 0.0
+        T = int(Ls.sum())
+        mk = lambda: torch.randn((T, heads, w.head_dim), device="cuda", dtype=torch.bfloat16, generator=gen)
+        q, k, v, do = mk(), mk(), mk(), mk()
+        cu = torch.from_numpy(np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)).cuda()
+        o, lse = binding.varlen_attn_fwd(q, k, v, cu, False, w.scale)
+
+        def step():
+            binding.varlen_attn_fwd(q, k, v, cu, False, w.scale, out=o, lse=lse)
+            binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, False, w.scale)
+        step()
+        ev = []
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            step()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+    print("| microbatch of the node | threshold | samples in SP state | slowest rank, DP state ms | SP state ms | total ms |")
+    print("|---|---|---|---|---|---|", flush=True)
+    for name, lengths in mixes.items():
+        for eta in (0, 1024, 2048, 4096, 8192, 16384, 1 << 30):
+            long_ = lengths[lengths > eta]
+            short = lengths[lengths <= eta]
+            t_dp = 0.0
+            if short.size:
+                # data-parallel state: whole samples, balanced over the ranks; the slowest rank counts
+                bin_of, cost = binding.balance_partition(short, ranks, binding.PARTITION_KARMARKAR_KARP)
+                t_dp = run(short[bin_of == int(np.argmax(cost))], model_heads)
+            # sequence-parallel state: every rank holds all tokens of the long samples for its heads
+            t_sp = run(long_, model_heads // ranks)
+            label = "all SP" if eta == 0 else ("all DP" if eta == 1 << 30 else str(eta))
+            print(f"| {name} | {label} | {long_.size} of {lengths.size} | {t_dp:.3f} | {t_sp:.3f} | {t_dp + t_sp:.3f} |",
+                  flush=True)
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -182,6 +234,11 @@ def main():
                          "mix) over 8 ranks as drawn, by greedy LPT and by Karmarkar-Karp differencing "
                          "(library's host-side partitioner, cost = L^2), run forward+backward on every "
                          "rank's share on this GPU and print max / mean share time as a markdown table")
+    ap.add_argument("--lssp", action="store_true",
+                    help="instead of the one JSON line: long-short sequence parallelism as ONE rank of an 8-rank "
+                         "node executes it: samples longer than a threshold run in the sequence-parallel state "
+                         "(full length, 1/8 of the heads), the others in the data-parallel state (this rank's "
+                         "balanced share, all heads); sweeps the threshold and prints a markdown table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
@@ -204,6 +261,9 @@ def main():
         return
     if args.balance:
         balance(args, torch, binding, W)
+        return
+    if args.lssp:
+        lssp(args, torch, binding, W)
         return
 
     with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5
