@@ -8,5 +8,6 @@ from .binding import (  # noqa: F401
     fwd,
     fwd_rows,
     bwd,
+    merge,
     num_threads,
 )

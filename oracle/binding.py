@@ -44,6 +44,8 @@ def _load():
                                                f64p, f64p, f64p]
         lib.oracle_varlen_attn_bwd.restype = ci
         lib.oracle_num_threads.restype = ci
+        lib.oracle_attn_merge.argtypes = [f32p, f64p, ci, ci, ci, ci, f64p, f64p]
+        lib.oracle_attn_merge.restype = ci
         _lib = lib
     return _lib
 
@@ -123,3 +125,20 @@ def bwd(q, k, v, dout, cu_seqlens, causal, scale):
     if rc:
         raise RuntimeError(f"oracle bwd failed with status {rc}")
     return dq, dk, dv
+
+
+def merge(o_parts, lse_parts):
+    """Combine partial results over disjoint key shards: o_parts [P,T,H,D], lse_parts [P,H,T] (-inf = the
+    shard held no key for that row).  Returns (O float64 [T,H,D], LSE float64 [H,T])."""
+    o_parts = np.ascontiguousarray(o_parts, dtype=np.float32)
+    P, T, H, D = o_parts.shape
+    lse_parts = np.ascontiguousarray(lse_parts, dtype=np.float64)
+    if lse_parts.shape != (P, H, T):
+        raise ValueError(f"expected lse_parts of shape {(P, H, T)}, got {lse_parts.shape}")
+    o = np.empty((T, H, D), dtype=np.float64)
+    lse = np.empty((H, T), dtype=np.float64)
+    rc = _load().oracle_attn_merge(_ptr(o_parts, ctypes.c_float), _ptr(lse_parts, ctypes.c_double), P, T, H, D,
+                                   _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_attn_merge failed with code {rc}")
+    return o, lse

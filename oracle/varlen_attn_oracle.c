@@ -278,3 +278,49 @@ int oracle_varlen_attn_bwd(const float *q, const float *k, const float *v, const
     free(delta);
     return failed ? ORACLE_NO_MEM : ORACLE_OK;
 }
+
+/*
+ * Merge of partial attention results over disjoint key/value shards.
+ *
+ * Where the paper needs it: context parallelism for overlong contexts (Section 4.1.2, 5D parallelism
+ * for the LLM; Section 5.2, adaptive sample sharding) leaves every rank with the attention
+ * of its queries over ONE shard of the keys; the full result is their combination.  The paper does
+ * not print it; it follows from the definition.  With part p holding, for one (query row, head),
+ *     O_p = sum_{j in shard p} exp(S_j - LSE_p) V_j,   LSE_p = ln sum_{j in shard p} exp(S_j)
+ * the result over the union of the shards is
+ *     LSE = ln sum_p exp(LSE_p),   O = sum_p exp(LSE_p - LSE) O_p.
+ * A part whose shard held no key for this row has LSE_p = -infinity and weight 0 (its O_p is not
+ * looked at); if every part is empty, O = 0 and LSE = -infinity.
+ *
+ * o_parts: float [P, T, H, D], lse_parts: double [P, H, T]; out o: double [T, H, D], lse: double [H, T].
+ */
+int oracle_attn_merge(const float *o_parts, const double *lse_parts, int P, int T, int H, int D,
+                      double *o, double *lse) {
+    if (P < 1 || T < 0 || H < 1 || D < 1 || !o_parts || !lse_parts || !o || !lse) return ORACLE_BAD_ARG;
+    for (int i = 0; i < T; ++i)
+        for (int h = 0; h < H; ++h) {
+            double mx = -INFINITY;
+            for (int p = 0; p < P; ++p) {
+                double x = lse_parts[((size_t)p * H + h) * T + i];
+                if (x > mx) mx = x;
+            }
+            double *orow = o + ((size_t)i * H + h) * D;
+            for (int d = 0; d < D; ++d) orow[d] = 0.0;
+            if (mx == -INFINITY) {
+                lse[(size_t)h * T + i] = -INFINITY;
+                continue;
+            }
+            double den = 0.0;
+            for (int p = 0; p < P; ++p) den += exp(lse_parts[((size_t)p * H + h) * T + i] - mx);
+            const double total = mx + log(den);
+            lse[(size_t)h * T + i] = total;
+            for (int p = 0; p < P; ++p) {
+                const double x = lse_parts[((size_t)p * H + h) * T + i];
+                if (x == -INFINITY) continue;
+                const double wgt = exp(x - total);
+                const float *prow = o_parts + (((size_t)p * T + i) * H + h) * D;
+                for (int d = 0; d < D; ++d) orow[d] += wgt * (double)prow[d];
+            }
+        }
+    return ORACLE_OK;
+}

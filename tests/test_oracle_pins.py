@@ -305,3 +305,62 @@ def test_config1_matches_brute_force_and_golden():
         a, b, c = int(a), int(b), int(c)
         got = o[a, b, c] if kind == "O" else lse[b, a]
         assert abs(got - float(val)) < 1e-12
+
+
+# --- merge of partial results over key shards (oracle.merge) ---
+
+def _partial_attention_numpy(q, k, v, keys, scale):
+    """Brute force for ONE sample and head: attention of every query over the key subset `keys`
+    (written independently of the C oracle: dense scores, no max subtraction; tiny inputs only)."""
+    if len(keys) == 0:
+        return np.zeros((q.shape[0], v.shape[1])), np.full(q.shape[0], -np.inf)
+    s = scale * (q.astype(np.float64) @ k[keys].astype(np.float64).T)
+    e = np.exp(s)
+    den = e.sum(1)
+    return (e @ v[keys].astype(np.float64)) / den[:, None], np.log(den)
+
+
+def test_merge_of_shard_results_is_full_attention():
+    import oracle
+    rng = np.random.default_rng(17)
+    L, D = 37, 16
+    q, k, v = (rng.standard_normal((L, 1, D)).astype(np.float32) for _ in range(3))
+    full_o, full_lse = oracle.fwd(q, k, v, np.array([0, L], np.int32), False, 0.3)
+    for shards in ([range(0, 20), range(20, 37)], [range(0, 1), range(1, 36), range(36, 37)],
+                   [list(range(0, 37, 2)), list(range(1, 37, 2))], [range(0, 37), []]):
+        parts = [_partial_attention_numpy(q[:, 0], k[:, 0], v[:, 0], list(sh), 0.3) for sh in shards]
+        o_parts = np.stack([p[0] for p in parts])[:, :, None, :]
+        lse_parts = np.stack([p[1] for p in parts])[:, None, :]
+        o, lse = oracle.merge(o_parts, lse_parts)
+        # o_parts pass through float32 on their way in: 1e-6 is that rounding, not the merge
+        assert np.abs(o - full_o).max() < 1e-6 and np.abs(lse - full_lse).max() < 1e-12
+
+
+def test_merge_special_cases():
+    import oracle
+    rng = np.random.default_rng(18)
+    o = rng.standard_normal((3, 5, 2, 4)).astype(np.float32)
+    lse = rng.standard_normal((3, 2, 5))
+    # one part: identity
+    m_o, m_lse = oracle.merge(o[:1], lse[:1])
+    assert np.array_equal(m_o, o[0].astype(np.float64)) and np.allclose(m_lse, lse[0], rtol=0, atol=1e-15)
+    # an empty part (-inf) changes nothing, wherever it stands and whatever garbage its O holds
+    empty_lse = np.full((1, 2, 5), -np.inf)
+    garbage = np.full((1, 5, 2, 4), np.nan, np.float32)
+    a_o, a_lse = oracle.merge(o[:2], lse[:2])
+    b_o, b_lse = oracle.merge(np.concatenate([o[:1], garbage, o[1:2]]), np.concatenate([lse[:1], empty_lse, lse[1:2]]))
+    assert np.array_equal(a_o, b_o) and np.array_equal(a_lse, b_lse)
+    # all parts empty: zero output, -inf
+    z_o, z_lse = oracle.merge(garbage, empty_lse)
+    assert np.all(z_o == 0) and np.all(np.isneginf(z_lse))
+    # equal LSEs: plain average and + ln P
+    same = np.repeat(lse[:1], 3, axis=0)
+    e_o, e_lse = oracle.merge(o, same)
+    assert np.allclose(e_o, o.astype(np.float64).mean(0), atol=1e-15) and np.allclose(e_lse, lse[0] + np.log(3.0), atol=1e-14)
+    # order of the parts does not matter; merging in two stages gives the same as in one
+    p_o, p_lse = oracle.merge(o[::-1], lse[::-1])
+    f_o, f_lse = oracle.merge(o, lse)
+    assert np.allclose(p_o, f_o, atol=1e-14) and np.allclose(p_lse, f_lse, atol=1e-14)
+    ab_o, ab_lse = oracle.merge(o[:2], lse[:2])
+    s_o, s_lse = oracle.merge(np.stack([ab_o.astype(np.float32), o[2]]), np.stack([ab_lse, lse[2]]))
+    assert np.abs(s_o - f_o).max() < 1e-6 and np.abs(s_lse - f_lse).max() < 1e-14
