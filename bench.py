@@ -216,6 +216,55 @@ def lssp(args, torch, binding, W, ranks=8, model_heads=16):
         torch.cuda.empty_cache()
 
 
+def small_launch(args, torch, binding, W):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+
+    def timed(fn, n=max(5, 20)):
+        fn()
+        ev = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+    print("| one sample of | heads (q/kv) | D | mask | workgroups unsplit | unsplit ms | automatic ms | speed-up |")
+    print("|---|---|---|---|---|---|---|---|", flush=True)
+    for L, Hq, Hkv, D, causal in ((2048, 2, 2, 128, True), (4096, 2, 2, 128, True), (8192, 2, 2, 80, False),
+                                  (8192, 4, 1, 128, True), (16384, 2, 2, 80, False), (32768, 2, 2, 80, False),
+                                  (65536, 2, 2, 80, False)):
+        mk = lambda h: torch.randn((L, h, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+        q, k, v = mk(Hq), mk(Hkv), mk(Hkv)
+        cu = torch.tensor([0, L], dtype=torch.int32, device="cuda")
+        scale = D ** -0.5
+        o = torch.empty_like(q)
+        lse = torch.empty((Hq, L), dtype=torch.float32, device="cuda")
+        res = []
+        for splits in (1, 0):
+            p = binding.make_params(L, 1, Hq, Hkv, D, causal, scale, splits)
+            ws = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+            res.append(timed(lambda: binding.varlen_attn_fwd(q, k, v, cu, causal, scale, out=o, lse=lse,
+                                                             workspace=ws, kv_splits=splits)))
+        print(f"| {L} tokens | {Hq}/{Hkv} | {D} | {'causal' if causal else 'full'} | {(L // 128) * Hq} | "
+              f"{res[0]:.3f} | {res[1]:.3f} | {res[0] / res[1]:.2f}x |", flush=True)
+    print()
+    print("| merge of | tokens x heads x D | algorithmic bytes | ms | GB/s | fraction of 8 TB/s |")
+    print("|---|---|---|---|---|---|", flush=True)
+    for P, T, H, D in ((2, 178572, 16, 64), (4, 178572, 16, 64), (2, 32768, 32, 128), (8, 65536, 2, 80)):
+        parts = torch.randn((P, T, H, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+        lses = torch.randn((P, H, T), device="cuda", dtype=torch.float32, generator=gen)
+        o = torch.empty((T, H, D), device="cuda", dtype=torch.bfloat16)
+        lse = torch.empty((H, T), device="cuda", dtype=torch.float32)
+        ms = timed(lambda: binding.varlen_attn_merge(parts, lses, out=o, lse=lse))
+        nbytes = (P + 1) * T * H * (2 * D + 4)  # every part read once, the result written once
+        print(f"| {P} parts | {T} x {H} x {D} | {nbytes / 1e9:.3f} GB | {ms:.4f} | {nbytes / ms / 1e6:.0f} | "
+              f"{nbytes / ms / 1e6 / 8000:.3f} |", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -239,6 +288,10 @@ def main():
                          "node executes it: samples longer than a threshold run in the sequence-parallel state "
                          "(full length, 1/8 of the heads), the others in the data-parallel state (this rank's "
                          "balanced share, all heads); sweeps the threshold and prints a markdown table")
+    ap.add_argument("--small-launch", action="store_true",
+                    help="instead of the one JSON line: forward on launches too small to fill the GPU with and "
+                         "without splitting each query tile's keys over several workgroups, and the merge "
+                         "primitive's HBM rate; prints markdown tables")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
@@ -264,6 +317,9 @@ def main():
         return
     if args.lssp:
         lssp(args, torch, binding, W)
+        return
+    if args.small_launch:
+        small_launch(args, torch, binding, W)
         return
 
     with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5

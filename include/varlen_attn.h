@@ -48,7 +48,8 @@ extern "C" {
 enum {
     VA_OK = 0,
     VA_ERR_NULL_PTR = 1,            /* a required pointer is NULL */
-    VA_ERR_BAD_SHAPE = 2,           /* negative size, heads < 1, Hq % Hkv != 0, causal not 0/1 */
+    VA_ERR_BAD_SHAPE = 2,           /* negative size or count, heads < 1, Hq % Hkv != 0, causal not 0/1,
+                                       kv_splits or num_parts out of range */
     VA_ERR_UNSUPPORTED = 3,         /* head_dim not in {64, 80, 96, 128}, or device is not gfx950 */
     VA_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below the *_workspace_bytes() answer */
     VA_ERR_BAD_SCALE = 5,           /* softmax_scale is NaN, infinite or negative */
@@ -64,8 +65,11 @@ typedef struct {
     int32_t head_dim;      /* D in {64, 80, 96, 128} */
     int32_t causal;        /* 0: full attention inside a sample; 1: j <= i inside a sample */
     float softmax_scale;   /* finite, >= 0 (0 is legal: uniform attention) */
-    int32_t reserved;      /* must be 0 */
+    int32_t kv_splits;     /* forward only, a tuning hint that never changes results beyond rounding:
+                              0 = automatic, 1 = never split, 2..VA_MAX_KV_SPLITS = that many
+                              workgroups share the keys of each query tile (see varlen_attn_fwd) */
 } varlen_attn_params;
+enum { VA_MAX_KV_SPLITS = 8, VA_MAX_MERGE_PARTS = 64 };
 
 /* Bytes of device scratch the forward / backward call needs for these sizes (0 on bad params). */
 size_t varlen_attn_fwd_workspace_bytes(const varlen_attn_params *p);
@@ -75,6 +79,10 @@ size_t varlen_attn_bwd_workspace_bytes(const varlen_attn_params *p);
  * Forward: writes o and lse.  Steps (all on the device): a length-aware scheduler turns
  * cu_seqlens into a list of 128-row query tiles ordered by decreasing cost; one workgroup per
  * (tile, head) streams the sample's K/V through LDS, S = QK^T and PV on bf16 MFMA, online softmax.
+ * A launch too small to fill the GPU (few heads, one mid-length sample: what a rank sees in the
+ * sequence-parallel state of Section 4.1.1) is split further: kv_splits workgroups share the keys of
+ * each query tile, write fp32 partial results into the workspace, and a merge kernel combines them
+ * (same formula as varlen_attn_merge).  The workspace size accounts for it.
  */
 int varlen_attn_fwd(const varlen_attn_params *p,
                     const void *q, const void *k, const void *v,
@@ -93,6 +101,22 @@ int varlen_attn_bwd(const varlen_attn_params *p,
                     const int32_t *cu_seqlens,
                     void *dq, void *dk, void *dv,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Merge of partial attention results over disjoint key/value shards: what context parallelism needs
+ * after every rank has attended to one shard of the keys (Section 4.1.2 selects context parallelism
+ * for overlong contexts; Section 5.2 shards long samples for it).  For every (row, head)
+ *     LSE = ln sum_p exp(LSE_p),    O = sum_p exp(LSE_p - LSE) * O_p.
+ * A part with LSE_p = -infinity held no key for that row: its weight is 0 and its O_p is not read.
+ * If all parts are empty, O = 0 and LSE = -infinity.
+ *   p          uses total_tokens, num_q_heads, head_dim (the other fields must still be valid)
+ *   o_parts    DEVICE bf16 [num_parts, total_tokens, num_q_heads, head_dim], 16-byte aligned
+ *   lse_parts  DEVICE fp32 [num_parts, num_q_heads, total_tokens]
+ *   o, lse     DEVICE outputs, bf16 [T, Hq, D] and fp32 [Hq, T]; must not alias the parts
+ * 1 <= num_parts <= VA_MAX_MERGE_PARTS.  Asynchronous on hip_stream, no workspace.
+ */
+int varlen_attn_merge(const varlen_attn_params *p, int32_t num_parts, const void *o_parts,
+                      const float *lse_parts, void *o, float *lse, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *varlen_attn_status_string(int status);
@@ -144,7 +168,8 @@ enum {
     VA_KERNEL_FWD = 1,   /* forward attention */
     VA_KERNEL_DELTA = 2, /* backward: Delta = rowsum(dO * O) */
     VA_KERNEL_DKDV = 3,  /* backward: dK, dV */
-    VA_KERNEL_DQ = 4     /* backward: dQ */
+    VA_KERNEL_DQ = 4,    /* backward: dQ */
+    VA_KERNEL_MERGE = 5  /* merge of partial results (varlen_attn_merge, split forward) */
 };
 int varlen_attn_profile_enable(int on);
 int varlen_attn_profile_read(int kernel, double *total_ms, int64_t *launches);

@@ -26,7 +26,7 @@ class Params(ctypes.Structure):
     _fields_ = [("total_tokens", ctypes.c_int32), ("num_seqs", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("causal", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32)]
+                ("softmax_scale", ctypes.c_float), ("kv_splits", ctypes.c_int32)]
 
 
 def load():
@@ -50,6 +50,8 @@ def load():
     lib.varlen_attn_fwd.restype = ctypes.c_int
     lib.varlen_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.varlen_attn_bwd.restype = ctypes.c_int
+    lib.varlen_attn_merge.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.varlen_attn_merge.restype = ctypes.c_int
     lib.varlen_attn_status_string.argtypes = [ctypes.c_int]
     lib.varlen_attn_status_string.restype = ctypes.c_char_p
     lib.varlen_attn_last_hip_error.argtypes = []
@@ -78,14 +80,14 @@ def _check(status):
         raise VarlenAttnError(status, msg)
 
 
-def make_params(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, causal, softmax_scale):
+def make_params(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, causal, softmax_scale, kv_splits=0):
     return Params(int(total_tokens), int(num_seqs), int(num_q_heads), int(num_kv_heads), int(head_dim),
-                  int(bool(causal)), float(softmax_scale), 0)
+                  int(bool(causal)), float(softmax_scale), int(kv_splits))
 
 
-def _params_of(q, k, cu_seqlens, causal, softmax_scale):
+def _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits=0):
     T, Hq, D = q.shape
-    return make_params(T, cu_seqlens.numel() - 1, Hq, k.shape[1], D, causal, softmax_scale)
+    return make_params(T, cu_seqlens.numel() - 1, Hq, k.shape[1], D, causal, softmax_scale, kv_splits)
 
 
 def _require(t, dtype, name):
@@ -111,13 +113,14 @@ def _stream_handle(stream):
 
 
 def varlen_attn_fwd(q, k, v, cu_seqlens, causal, softmax_scale, out=None, lse=None, workspace=None,
-                    stream=None):
-    """O bf16 [T,Hq,D] and LSE fp32 [Hq,T] of packed attention; asynchronous on the stream."""
+                    stream=None, kv_splits=0):
+    """O bf16 [T,Hq,D] and LSE fp32 [Hq,T] of packed attention; asynchronous on the stream.
+    kv_splits: 0 automatic, 1 never, 2..8 workgroups sharing the keys of each query tile."""
     lib = load()
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
     _require(cu_seqlens, torch.int32, "cu_seqlens")
-    p = _params_of(q, k, cu_seqlens, causal, softmax_scale)
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits)
     if k.shape != v.shape or k.shape[0] != q.shape[0] or k.shape[2] != q.shape[2]:
         raise ValueError("k and v must be [T, Hkv, D] matching q's T and D")
     if out is None:
@@ -157,7 +160,7 @@ def varlen_attn_bwd(dout, q, k, v, out, lse, cu_seqlens, causal, softmax_scale, 
     return dq, dk, dv
 
 
-KERNELS = {"sched": 0, "fwd": 1, "delta": 2, "dkdv": 3, "dq": 4}
+KERNELS = {"sched": 0, "fwd": 1, "delta": 2, "dkdv": 3, "dq": 4, "merge": 5}
 
 
 def profile_enable(on=True):
@@ -172,6 +175,23 @@ def profile_read():
         _check(load().varlen_attn_profile_read(kid, ctypes.byref(ms), ctypes.byref(n)))
         out[name] = (ms.value, n.value)
     return out
+
+
+def varlen_attn_merge(o_parts, lse_parts, out=None, lse=None, stream=None):
+    """Merge partial results over key shards: o_parts bf16 [P,T,Hq,D], lse_parts fp32 [P,Hq,T]."""
+    _require(o_parts, torch.bfloat16, "o_parts")
+    _require(lse_parts, torch.float32, "lse_parts")
+    P, T, Hq, D = o_parts.shape
+    if tuple(lse_parts.shape) != (P, Hq, T):
+        raise ValueError("lse_parts must be [P, Hq, T]")
+    p = make_params(T, 1, Hq, Hq, D, False, 1.0)
+    if out is None:
+        out = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=o_parts.device)
+    if lse is None:
+        lse = torch.empty((Hq, T), dtype=torch.float32, device=o_parts.device)
+    _check(load().varlen_attn_merge(ctypes.byref(p), P, o_parts.data_ptr(), lse_parts.data_ptr(), out.data_ptr(),
+                                    lse.data_ptr(), _stream_handle(stream)))
+    return out, lse
 
 
 PARTITION_KARMARKAR_KARP = 0

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvarlen_attn.so")
-SOURCES = ["va_api.hip", "va_sched.hip", "va_fwd.hip", "va_bwd.hip", "va_partition.hip"]
+SOURCES = ["va_api.hip", "va_sched.hip", "va_fwd.hip", "va_bwd.hip", "va_partition.hip", "va_merge.hip"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form v_pk_*_f32 from float code.
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores use a finite
 # sentinel), and without it every fmaxf of an MFMA result costs an extra canonicalising v_max.
@@ -29,7 +29,7 @@ def _compile(src):
 
 def build():
     os.makedirs(os.path.join(CSRC, "_build"), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB

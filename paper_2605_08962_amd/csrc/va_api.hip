@@ -1,4 +1,5 @@
 // C-ABI entry points of libvarlen_attn.so: argument validation, workspace carving, launches.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -53,14 +54,15 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 int check_params(const varlen_attn_params* p) {
     if (!p) return VA_ERR_NULL_PTR;
     if (p->total_tokens < 0 || p->num_seqs < 0 || p->num_q_heads < 1 || p->num_kv_heads < 1 ||
-        p->num_q_heads % p->num_kv_heads != 0 || (p->causal != 0 && p->causal != 1) || p->reserved != 0)
+        p->num_q_heads % p->num_kv_heads != 0 || (p->causal != 0 && p->causal != 1) || p->kv_splits < 0 ||
+        p->kv_splits > VA_MAX_KV_SPLITS)
         return VA_ERR_BAD_SHAPE;
     if (p->head_dim != 64 && p->head_dim != 80 && p->head_dim != 96 && p->head_dim != 128)
         return VA_ERR_UNSUPPORTED;
     if (!std::isfinite(p->softmax_scale) || p->softmax_scale < 0.f) return VA_ERR_BAD_SCALE;
     // grid sizes and packed offsets are 32-bit in places: keep the launch within them
     int64_t items = (int64_t)p->total_tokens / 64 + p->num_seqs;
-    if (items * p->num_q_heads >= (int64_t)1 << 31) return VA_ERR_BAD_SHAPE;
+    if (items * p->num_q_heads * std::max(p->kv_splits, 1) >= (int64_t)1 << 31) return VA_ERR_BAD_SHAPE;
     return VA_OK;
 }
 
@@ -78,6 +80,37 @@ int check_device() {
     checked_dev = dev;
     checked_rc = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? VA_OK : VA_ERR_UNSUPPORTED;
     return checked_rc;
+}
+
+// How many workgroups share the keys of one query tile in the forward.  Splitting only pays when the
+// launch cannot fill the chip: fewer workgroups than the 256 CUs can hold at once (3 per CU at
+// head_dim <= 64, else 2), and samples long enough that every chunk still gets two key tiles.
+int fwd_kv_splits(const varlen_attn_params* p) {
+    if (p->kv_splits >= 1) return p->kv_splits;
+    const int64_t wgs = ((int64_t)p->total_tokens / va::FWD_TILE_Q + p->num_seqs) * p->num_q_heads;
+    const int64_t slots = 256 * (p->head_dim <= 64 ? 3 : 2);
+    const int64_t tiles_per_sample = (int64_t)p->total_tokens / p->num_seqs / va::FWD_TILE_KV;
+    int64_t s = std::min<int64_t>(std::min<int64_t>(slots / std::max<int64_t>(wgs, 1), tiles_per_sample / 2), VA_MAX_KV_SPLITS);
+    return (int)std::max<int64_t>(s, 1);
+}
+
+struct FwdLayout {
+    va::SchedLayout sched;
+    int splits;
+    size_t part_o_ofs, part_lse_ofs, end;
+};
+
+FwdLayout fwd_layout(const varlen_attn_params* p) {
+    FwdLayout f;
+    f.sched = va::sched_layout(p->total_tokens, p->num_seqs, va::FWD_TILE_Q);
+    f.splits = fwd_kv_splits(p);
+    f.part_o_ofs = f.part_lse_ofs = f.end = f.sched.end_ofs;
+    if (f.splits > 1) {
+        const size_t rows = (size_t)p->total_tokens * p->num_q_heads;
+        f.part_lse_ofs = f.part_o_ofs + (size_t)f.splits * rows * p->head_dim * sizeof(float);
+        f.end = (f.part_lse_ofs + (size_t)f.splits * rows * sizeof(float) + 255) / 256 * 256;
+    }
+    return f;
 }
 
 struct BwdLayout {
@@ -102,7 +135,8 @@ extern "C" {
 
 size_t varlen_attn_fwd_workspace_bytes(const varlen_attn_params* p) {
     if (check_params(p) != VA_OK) return 0;
-    return va::sched_layout(p->total_tokens, p->num_seqs, va::FWD_TILE_Q).end_ofs;
+    if (p->total_tokens == 0 || p->num_seqs == 0) return va::sched_layout(0, 0, va::FWD_TILE_Q).end_ofs;
+    return fwd_layout(p).end;
 }
 
 size_t varlen_attn_bwd_workspace_bytes(const varlen_attn_params* p) {
@@ -126,8 +160,9 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(workspace) ||
         ((uintptr_t)lse & 3u) || ((uintptr_t)cu_seqlens & 3u))
         return VA_ERR_MISALIGNED;
-    va::SchedLayout lay = va::sched_layout(p->total_tokens, p->num_seqs, va::FWD_TILE_Q);
-    if (workspace_bytes < lay.end_ofs) return VA_ERR_WORKSPACE_TOO_SMALL;
+    const FwdLayout fl = fwd_layout(p);
+    const va::SchedLayout& lay = fl.sched;
+    if (workspace_bytes < fl.end) return VA_ERR_WORKSPACE_TOO_SMALL;
     rc = check_device();
     if (rc != VA_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -146,10 +181,38 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     a.max_items = lay.max_items;
     a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
+    a.kv_splits = fl.splits;
+    a.part_o = (float*)((char*)workspace + fl.part_o_ofs);
+    a.part_lse = (float*)((char*)workspace + fl.part_lse_ofs);
     {
         ProfScope ps(VA_KERNEL_FWD, stream);
         e = va::launch_fwd(a, stream);
     }
+    if (e != hipSuccess) return hip_fail(e);
+    if (fl.splits > 1) {
+        ProfScope ps(VA_KERNEL_MERGE, stream);
+        e = va::launch_merge(a.part_o, true, a.part_lse, fl.splits, p->total_tokens, p->num_q_heads, p->head_dim,
+                             o, lse, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return VA_OK;
+}
+
+int varlen_attn_merge(const varlen_attn_params* p, int32_t num_parts, const void* o_parts, const float* lse_parts,
+                      void* o, float* lse, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != VA_OK) return rc;
+    if (num_parts < 1 || num_parts > VA_MAX_MERGE_PARTS) return VA_ERR_BAD_SHAPE;
+    if (p->total_tokens == 0) return VA_OK;
+    if (!o_parts || !lse_parts || !o || !lse) return VA_ERR_NULL_PTR;
+    if (!aligned16(o_parts) || !aligned16(o) || ((uintptr_t)lse & 3u) || ((uintptr_t)lse_parts & 3u))
+        return VA_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != VA_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    ProfScope ps(VA_KERNEL_MERGE, stream);
+    hipError_t e = va::launch_merge(o_parts, false, lse_parts, num_parts, p->total_tokens, p->num_q_heads,
+                                    p->head_dim, o, lse, stream);
     if (e != hipSuccess) return hip_fail(e);
     return VA_OK;
 }
@@ -224,7 +287,7 @@ const char* varlen_attn_status_string(int status) {
     switch (status) {
         case VA_OK: return "ok";
         case VA_ERR_NULL_PTR: return "a required pointer is NULL";
-        case VA_ERR_BAD_SHAPE: return "bad shape: negative size, head counts, causal flag, reserved field or launch too large";
+        case VA_ERR_BAD_SHAPE: return "bad shape: negative size or count, head counts, causal flag, kv_splits, or launch too large";
         case VA_ERR_UNSUPPORTED: return "unsupported: head_dim must be 64, 80, 96 or 128 and the device gfx950";
         case VA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case VA_ERR_BAD_SCALE: return "softmax_scale must be finite and >= 0";

@@ -188,16 +188,22 @@ template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (D <= 64 ? 3 : 2))
 fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
            __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
-           const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale) {
+           const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale, int S,
+           float* __restrict__ part_o, float* __restrict__ part_lse) {
     using C = FwdCfg<D>;
     using LT = LdsTile<D>;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * C::TILE];  // K x3, then V x2
 
-    const int item = blockIdx.x / Hq;
+    // S > 1: the key tiles of every query tile are split into S consecutive chunks, one workgroup
+    // each, which write partial results (fp32 O and LSE per chunk) that a merge kernel combines.  Used
+    // for launches too small to fill the chip (few heads, one mid-length sample).
+    const int ch = S > 1 ? (int)(blockIdx.x % S) : 0;
+    const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
+    const int item = bid / Hq;
     if (item >= hdr[0]) return;
     // Heads: consecutive workgroups walk the kv heads first, so that (with Hkv a multiple of the
     // 8 XCDs) every XCD's L2 only ever sees its own kv heads.
-    const int hp = blockIdx.x % Hq;
+    const int hp = bid % Hq;
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
@@ -215,6 +221,11 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // causal mask, entirely at or below the tile's first query row
     const int n_plain = CAUSAL ? min(L, q0 + 1) / C::BKV : L / C::BKV;
     const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;  // this wave's query rows
+    const int jb = S > 1 ? ntiles * ch / S : 0, je = S > 1 ? ntiles * (ch + 1) / S : ntiles;  // this chunk's tiles
+    if (jb >= je) {  // fewer tiles than chunks: an empty part (its O is never read)
+        if (qvalid && hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = -INFINITY;
+        return;
+    }
 
     const unsigned char* kbase = (const unsigned char*)(K + ((size_t)sb * Hkv + kvh) * D);
     const unsigned char* vbase = (const unsigned char*)(V + ((size_t)sb * Hkv + kvh) * D);
@@ -248,9 +259,9 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // prologue: K(0), V(0), K(1) and this lane's Q fragments.  Everything is waited for here, once:
     // the compiler cannot see the direct-to-LDS loads, and if the Q loads were still pending in its
     // bookkeeping at loop entry it would put a wait for ALL outstanding loads into every iteration.
-    load_k(0, 0);
-    load_v(0, 0);
-    if (ntiles > 1) load_k(1, 1);
+    load_k(jb, 0);
+    load_v(jb, 0);
+    if (jb + 1 < je) load_k(jb + 1, 1);
     bf16x8 qf[C::KS];
     {
         const __bf16* qp = Q + ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
@@ -263,28 +274,30 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     wait_vmcnt<0>();
     wg_barrier();
 
-    int kslot = 0;  // j % 3
-    int j = 0;
+    int kslot = 0;  // (j - jb) % 3
+    int vslot = 0;  // (j - jb) % 2
+    int j = jb;
     // Issue the prefetches of iteration j, return the LDS tiles of iteration j.
 #define VA_FWD_ITER_BEGIN()                                                                \
         const int kv0 = j * C::BKV;                                                            \
-        if (j + 1 < ntiles) load_v(j + 1, (j + 1) & 1);                                        \
-        if (j + 2 < ntiles) load_k(j + 2, kslot == 0 ? 2 : kslot - 1); /* slot (j + 2) % 3 */ \
+        if (j + 1 < je) load_v(j + 1, vslot ^ 1);                                              \
+        if (j + 2 < je) load_k(j + 2, kslot == 0 ? 2 : kslot - 1); /* slot (j + 2 - jb) % 3 */ \
         const unsigned char* kb = kbuf + kslot * C::TILE;                                      \
-        const unsigned char* vb = vbuf + (j & 1) * C::TILE;
+        const unsigned char* vb = vbuf + vslot * C::TILE;
     // K(j+1) and V(j+1) must have landed; K(j+2), issued last, may stay in flight.
 #define VA_FWD_ITER_END()                                                                  \
-        if (j + 2 < ntiles) wait_vmcnt<C::NI>(); else wait_vmcnt<0>();                         \
+        if (j + 2 < je) wait_vmcnt<C::NI>(); else wait_vmcnt<0>();                             \
         wg_barrier();                                                                          \
-        kslot = kslot == 2 ? 0 : kslot + 1;
+        kslot = kslot == 2 ? 0 : kslot + 1;                                                    \
+        vslot ^= 1;
 
-    if (j < n_plain) {  // the first mask-free tile sets the reference maximum
+    if (j < min(n_plain, je)) {  // the first mask-free tile sets the reference maximum
         VA_FWD_ITER_BEGIN()
         tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
         VA_FWD_ITER_END()
         ++j;
     }
-    for (; j < n_plain; ++j) {  // no masks, every wave active, maximum taken on trust
+    for (; j < min(n_plain, je); ++j) {  // no masks, every wave active, maximum taken on trust
         VA_FWD_ITER_BEGIN()
         // (measured: worth 2 % at head_dim 64 and 80, where the vector ALU is the busier pipe; at 128
         // the matrix pipe is, and the second code path only costs registers)
@@ -292,7 +305,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
             tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
         VA_FWD_ITER_END()
     }
-    for (; j < ntiles; ++j) {  // the sample's ragged last tile and the causal diagonal
+    for (; j < je; ++j) {  // the sample's ragged last tile and the causal diagonal
         VA_FWD_ITER_BEGIN()
         // causal: a wave whose rows all lie above this key tile has nothing to add
         if (!CAUSAL || kv0 <= wq_hi) {
@@ -310,8 +323,25 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // The row sum stays in fp32 on the vector ALU: summing the bf16-rounded P on the matrix cores
     // instead was measured to cost up to 1e-3 in LSE, the whole tolerance.
     const float ltot = xhalf_sum(lsum);
-    const float inv = 1.f / ltot;
+    // (a row can have met no key at all only in a chunk of a split launch: under the causal mask
+    // the chunk may lie entirely beyond the row; its part is empty)
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    const float row_lse = ltot > 0.f ? m * scale + __logf(ltot) : -INFINITY;
     if (qvalid) {
+        if (S > 1) {
+            float* op = part_o + (((size_t)ch * T + sb + qrow) * Hq + h) * D;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    int d0 = 32 * db + 8 * r4 + 4 * hh;
+                    if (d0 < D)
+                        *(float4*)(op + d0) = make_float4(oacc[db][4 * r4 + 0] * inv, oacc[db][4 * r4 + 1] * inv,
+                                                          oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
+                }
+            if (hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = row_lse;
+            return;
+        }
         __bf16* op = O + ((size_t)(sb + qrow) * Hq + h) * D;
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
@@ -325,20 +355,22 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
                     *(bf16x4*)(op + d0) = o4;
                 }
             }
-        if (hh == 0) LSE[(size_t)h * T + sb + qrow] = m * scale + __logf(ltot);
+        if (hh == 0) LSE[(size_t)h * T + sb + qrow] = row_lse;
     }
 }
 
 template <int D>
 static hipError_t launch_d(const FwdArgs& a, hipStream_t stream) {
-    dim3 grid((unsigned)(a.max_items * a.num_q_heads)), block(256);
+    dim3 grid((unsigned)(a.max_items * a.num_q_heads * a.kv_splits)), block(256);
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
     if (a.causal)
         hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
-                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale);
+                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
+                           a.kv_splits, a.part_o, a.part_lse);
     else
         hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
-                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale);
+                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
+                           a.kv_splits, a.part_o, a.part_lse);
     return hipGetLastError();
 }
 

@@ -41,6 +41,9 @@ struct FwdArgs {
     int64_t max_items;
     int total_tokens, num_q_heads, num_kv_heads, head_dim, causal;
     float scale;
+    int kv_splits;    // >= 1; > 1: every query tile's keys are split over that many workgroups
+    float* part_o;    // kv_splits > 1: fp32 [kv_splits, T, Hq, D] partial outputs
+    float* part_lse;  // kv_splits > 1: fp32 [kv_splits, Hq, T]
 };
 constexpr int FWD_TILE_Q = 128;
 constexpr int FWD_TILE_KV = 64;
@@ -64,6 +67,10 @@ constexpr int BWD_TILE_KV = 128;  // rows of K/V one dK/dV workgroup owns
 constexpr int BWD_STEP_Q = 64;    // query rows it stages per step
 constexpr int BWD_TILE_Q = 128;   // rows of Q one dQ workgroup owns
 constexpr int BWD_STEP_KV = 64;   // key rows it stages per step
+// O = sum_p exp(LSE_p - LSE) O_p over parts [P, T, H, D] (bf16 or fp32) with lse [P, H, T].
+hipError_t launch_merge(const void* o_parts, bool parts_fp32, const float* lse_parts, int P, int T, int H, int D,
+                        void* o, float* lse, hipStream_t stream);
+
 hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream);

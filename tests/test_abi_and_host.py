@@ -37,7 +37,7 @@ def test_params_struct_matches_header():
     from paper_2605_08962_amd import binding
     assert ctypes.sizeof(binding.Params) == 32
     assert [f[0] for f in binding.Params._fields_] == [
-        "total_tokens", "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "causal", "softmax_scale", "reserved"]
+        "total_tokens", "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "causal", "softmax_scale", "kv_splits"]
 
 
 def test_status_strings(lib):
@@ -62,8 +62,9 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert _call_fwd(lib, mk(8, 1, 2, 0, 64, 0, 0.125)) == 2
     p = mk(8, 1, 2, 2, 64, 0, 0.125); p.causal = 2
     assert _call_fwd(lib, p) == 2
-    p = mk(8, 1, 2, 2, 64, 0, 0.125); p.reserved = 1
-    assert _call_fwd(lib, p) == 2
+    for bad in (-1, 9):
+        p = mk(8, 1, 2, 2, 64, 0, 0.125); p.kv_splits = bad
+        assert _call_fwd(lib, p) == 2
     for d in (0, 32, 48, 72, 256):
         assert _call_fwd(lib, mk(8, 1, 2, 2, d, 0, 0.125)) == 3
     for s in (float("nan"), float("inf"), -0.5):

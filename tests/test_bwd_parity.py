@@ -85,14 +85,15 @@ def test_packed_equals_alone():
     from paper_2605_08962_amd import binding
     w = W.make_custom([200, 64, 333], 4, 2, 64, True, seed=71, with_dout=True)
     d = upload(w)
-    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], True, w.scale)
+    # (the forward with kv_splits=1 so that the saved O and LSE are bit-identical in both settings)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], True, w.scale, kv_splits=1)
     dq, dk, dv = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], True, w.scale)
     cu = w.cu_seqlens
     for s in range(3):
         a, b = int(cu[s]), int(cu[s + 1])
         one = torch.tensor([0, b - a], dtype=torch.int32, device="cuda")
         sl = lambda t: t[a:b].contiguous()
-        o1, lse1 = binding.varlen_attn_fwd(sl(d["q"]), sl(d["k"]), sl(d["v"]), one, True, w.scale)
+        o1, lse1 = binding.varlen_attn_fwd(sl(d["q"]), sl(d["k"]), sl(d["v"]), one, True, w.scale, kv_splits=1)
         dq1, dk1, dv1 = binding.varlen_attn_bwd(sl(d["dout"]), sl(d["q"]), sl(d["k"]), sl(d["v"]), o1, lse1, one, True, w.scale)
         assert torch.equal(dq1, dq[a:b]) and torch.equal(dk1, dk[a:b]) and torch.equal(dv1, dv[a:b])
 

@@ -98,14 +98,21 @@ def test_packed_equals_alone_and_order_free():
     from paper_2605_08962_amd import binding
     w = W.make_custom([200, 64, 333], 4, 2, 64, False, seed=17)
     d = upload(w)
-    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], False, w.scale)
+    # (kv_splits=1: how many workgroups share a query tile's keys is chosen from the size of the
+    # launch and changes the rounding; with that fixed, a sample's results are bit-identical whatever
+    # it is packed with)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], False, w.scale, kv_splits=1)
     cu = w.cu_seqlens
     for s in range(3):
         a, b = int(cu[s]), int(cu[s + 1])
         one = torch.tensor([0, b - a], dtype=torch.int32, device="cuda")
         o1, lse1 = binding.varlen_attn_fwd(d["q"][a:b].contiguous(), d["k"][a:b].contiguous(),
-                                           d["v"][a:b].contiguous(), one, False, w.scale)
+                                           d["v"][a:b].contiguous(), one, False, w.scale, kv_splits=1)
         assert torch.equal(o1, o[a:b]) and torch.equal(lse1, lse[:, a:b])
+        o2, lse2 = binding.varlen_attn_fwd(d["q"][a:b].contiguous(), d["k"][a:b].contiguous(),
+                                           d["v"][a:b].contiguous(), one, False, w.scale)
+        assert float((o2.float() - o[a:b].float()).abs().max()) <= 2.0 ** -6
+        assert float((lse2 - lse[:, a:b]).abs().max()) <= 1e-4
 
 
 def test_empty_inputs_and_errors():
