@@ -646,6 +646,47 @@ __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned 
         }
 }
 
+// ---- the mask-free dQ step in phases (see the dK/dV kernel): S | dP with exp in its shadow | dQ
+// with dS in its shadow; the LDS operands of a phase are read one phase ahead ----
+template <int D>
+struct DqOpsA {  // operands of S^T = K Q^T or dP^T = V dO^T for the step's two 32-key blocks
+    bf16x8 a[2][BwdCfg<D>::KS];
+};
+template <int D>
+struct DqOpsT {  // K^T operands of dQ^T += K^T dS^T: key block b, 16-key step st, 32-channel block db
+    bf16x8 a[2][2][BwdCfg<D>::DB];
+};
+template <int D>
+__device__ __forceinline__ void dq_load_A(const unsigned char* tile, const int (&aaddr)[BwdCfg<D>::KS], DqOpsA<D>& f) {
+    constexpr int ROWB = BwdCfg<D>::T::ROWB;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int ks = 0; ks < BwdCfg<D>::KS; ++ks) f.a[b][ks] = *(const bf16x8*)(tile + aaddr[ks] + b * 32 * ROWB);
+}
+template <int D>
+__device__ __forceinline__ void dq_load_T(const unsigned char* kt, const int (&taddr)[BwdCfg<D>::DB][2], DqOpsT<D>& f) {
+    constexpr int ROWB = BwdCfg<D>::T::ROWB;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int db = 0; db < BwdCfg<D>::DB; ++db) {
+                const unsigned char* p0 = kt + (32 * b + 16 * st) * ROWB;
+                f.a[b][st][db] = cat4(lds_read_tr(p0 + taddr[db][0]), lds_read_tr(p0 + taddr[db][1]));
+            }
+}
+// acc[b] = init + sum_ks ops[b][ks] x frag[ks]
+template <int D>
+__device__ __forceinline__ void dq_run_A(const DqOpsA<D>& f, const bf16x8 (&frag)[BwdCfg<D>::KS], const f32x16& init,
+                                         f32x16 (&acc)[2]) {
+#pragma unroll
+    for (int ks = 0; ks < BwdCfg<D>::KS; ++ks)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[b] = mfma32(f.a[b][ks], frag[ks], ks == 0 ? init : acc[b]);
+}
+
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
@@ -655,7 +696,9 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[3 * STAGE];
+    constexpr int NST = 4;              // LDS stages
+    constexpr int PER = 2 * C::NI;      // loads per wave per step
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int item = blockIdx.x / Hq;
     if (item >= hdr[0]) return;
@@ -680,9 +723,31 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     TileDma<D, 64> dma;
     dma.init(row_bytes, L, w, l);
     const uint32_t lds0 = lds_address(lds);
-    auto load_kv = [&](int j, int stage) {
-        dma.issue(kbase, row_bytes, j * BWD_STEP_KV, L, lds0 + stage * STAGE, w);
-        dma.issue(vbase, row_bytes, j * BWD_STEP_KV, L, lds0 + stage * STAGE + C::TILE, w);
+    // Staging, as in the dK/dV kernel: pointers advanced by additions, loads issued unconditionally
+    // (after the last step the same step is fetched again into a stage nobody reads), so that every
+    // step has the same number of loads in flight and the loop needs no branches around them.
+    const int64_t step_bytes = (int64_t)BWD_STEP_KV * row_bytes;
+    const bool ragged_sample = (L % BWD_STEP_KV) != 0;
+    const int last_step = (L + BWD_STEP_KV - 1) / BWD_STEP_KV - 1;  // the one holding the sample's end
+    const unsigned char *nxt_k = kbase, *nxt_v = vbase;
+    int nxt_j = 0, iss_stage = 0;
+    bool iss_ragged = false;
+    const unsigned char *iss_k = nullptr, *iss_v = nullptr;
+    uint32_t iss_lds = 0;
+    auto begin_issue = [&]() {
+        iss_k = nxt_k; iss_v = nxt_v;
+        iss_ragged = ragged_sample && nxt_j == last_step;
+        iss_lds = lds0 + iss_stage * STAGE;
+        iss_stage = iss_stage == NST - 1 ? 0 : iss_stage + 1;
+        const bool more = nxt_j + 1 < nsteps;
+        const int64_t adv = more ? step_bytes : 0;
+        nxt_k += adv; nxt_v += adv;
+        nxt_j += more ? 1 : 0;
+    };
+    auto issue_all = [&]() {
+        begin_issue();
+        dma.issue_tile(iss_k, iss_ragged, iss_lds, w);
+        dma.issue_tile(iss_v, iss_ragged, iss_lds + C::TILE, w);
     };
 
     int aaddr[C::KS], taddr[C::DB][2];
@@ -694,8 +759,9 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
         taddr[db][1] = LT::tr_off(l, 8, db);
     }
 
-    load_kv(0, 0);
-    if (nsteps > 1) load_kv(1, 1);
+    issue_all();
+    issue_all();
+    issue_all();
     bf16x8 qf[C::KS], dof[C::KS];
     float lse2 = 0.f, ndelta = 0.f;  // ndelta = -Delta
     {
@@ -723,32 +789,79 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     const float c2 = scale * kLog2e;
     const int wq_hi = q0 + 32 * w + 31;
 
+    // Stage protocol as in the dK/dV kernel: step i lives in stage i % 4; VA_DQ_SYNC() waits until step
+    // j + 1 has landed (step j + 2 may stay in flight) and passes the barrier after which stage j - 1
+    // is free for step j + 3.
     int stage_i = 0;
     int j = 0;
-#define VA_DQ_BEGIN()                                                                     \
-        const int kv0 = j * BWD_STEP_KV;                                                      \
-        if (j + 2 < nsteps) load_kv(j + 2, stage_i == 0 ? 2 : stage_i - 1);                   \
-        const unsigned char* b = lds + stage_i * STAGE;
-#define VA_DQ_END()                                                                       \
-        if (j + 2 < nsteps) wait_vmcnt<2 * C::NI>(); else wait_vmcnt<0>();                    \
-        wg_barrier();                                                                         \
-        stage_i = stage_i == 2 ? 0 : stage_i + 1;
+#define VA_DQ_SYNC()      \
+        wait_vmcnt<PER>();    \
+        wg_barrier();
+#define VA_DQ_ADVANCE() stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
+#define VA_DQ_CAREFUL()                                                                           \
+    {                                                                                                 \
+        const int kv0 = j * BWD_STEP_KV;                                                              \
+        const unsigned char* b = lds + stage_i * STAGE;                                               \
+        /* causal: a wave whose rows all lie above this key step has nothing to add; every other step \
+           here takes the masked variant (a superset of the plain one) to keep the code small */      \
+        if (!CAUSAL || kv0 <= wq_hi)                                                                  \
+            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh); \
+        VA_DQ_SYNC()                                                                                  \
+        issue_all();                                                                                  \
+        VA_DQ_ADVANCE()                                                                               \
+    }
 
-    for (; j < n_plain; ++j) {
-        VA_DQ_BEGIN()
-        dq_step<D, CAUSAL, false>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh);
-        VA_DQ_END()
+    if (j < n_plain) {
+        f32x16 nd16, zero16;  // -Delta of this lane's row as the starting value of dP; 0 for S
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { nd16[r] = ndelta; zero16[r] = 0.f; }
+        DqOpsA<D> fa;  // K rows for S, then V rows for dP
+        DqOpsA<D> fv;
+        DqOpsT<D> ft;
+        f32x16 s[2], dp[2];
+        dq_load_A<D>(lds + stage_i * STAGE, aaddr, fa);
+        for (; j < n_plain; ++j) {
+            VA_DQ_SYNC()
+            const unsigned char* cur = lds + stage_i * STAGE;
+            const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
+            // S^T = K Q^T; meanwhile fetch the V rows and do the scalar bookkeeping of this step's loads
+            dq_load_A<D>(cur + C::TILE, aaddr, fv);
+            dq_run_A<D>(fa, qf, zero16, s);
+            begin_issue();
+            __builtin_amdgcn_sched_barrier(0);
+            dma.issue_tile(iss_k, iss_ragged, iss_lds, w);
+            // dP^T = V dO^T - Delta with P = exp2(c2 S - lse2) in its shadow; meanwhile fetch K^T
+            dq_load_T<D>(cur, taddr, ft);
+            dq_run_A<D>(fv, dof, nd16, dp);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[b][r] = fast_exp2(__builtin_fmaf(s[b][r], c2, -lse2));
+            dkdv_interleave<2 * C::KS, 4 * C::DB / C::KS, 8>();
+            __builtin_amdgcn_sched_barrier(0);
+            dma.issue_tile(iss_v, iss_ragged, iss_lds + C::TILE, w);
+            // dQ^T += K^T dS^T with dS = P (dP - Delta) in its shadow; meanwhile fetch the next step's K rows
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dp[b][8 * st + e] *= s[b][8 * st + e];
+                    const bf16x8 dsb = pack_regs(dp[b], st);
+#pragma unroll
+                    for (int db = 0; db < C::DB; ++db) dqacc[db] = mfma32(ft.a[b][st][db], dsb, dqacc[db]);
+                }
+            dq_load_A<D>(nxt, aaddr, fa);
+            dkdv_interleave<4 * C::DB, 2 * C::KS / (4 * C::DB) + 1, 6>();
+            __builtin_amdgcn_sched_barrier(0);
+            VA_DQ_ADVANCE()
+        }
     }
-    for (; j < nsteps; ++j) {
-        VA_DQ_BEGIN()
-        // causal: a wave whose rows all lie above this key step has nothing to add; every other step
-        // here takes the masked variant (a superset of the plain one) to keep the code small
-        if (!CAUSAL || kv0 <= wq_hi)
-            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh);
-        VA_DQ_END()
-    }
-#undef VA_DQ_BEGIN
-#undef VA_DQ_END
+    for (; j < nsteps; ++j) VA_DQ_CAREFUL()
+    wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
+#undef VA_DQ_SYNC
+#undef VA_DQ_ADVANCE
+#undef VA_DQ_CAREFUL
 
     if (qvalid) {
         __bf16* dqp = dQ + ((size_t)(sb + qrow) * Hq + h) * D;
