@@ -27,10 +27,25 @@ def _compile(src):
     return obj
 
 
+UBENCH = os.path.join(HERE, "ubench_mfma_valu")
+
+
+def build_ubench():
+    """The stand-alone MFMA / vector-ALU overlap microbenchmark (csrc/ubench_mfma_valu.hip)."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "ubench_mfma_valu.hip"), "-o", UBENCH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on ubench_mfma_valu.hip:\n" + r.stderr)
+    return UBENCH
+
+
 def build():
     os.makedirs(os.path.join(CSRC, "_build"), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
+        ub = ex.submit(build_ubench)
         objs = list(ex.map(_compile, SOURCES))
+        ub.result()
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB
 
