@@ -308,13 +308,10 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     for (; j < je; ++j) {  // the sample's ragged last tile and the causal diagonal
         VA_FWD_ITER_BEGIN()
         // causal: a wave whose rows all lie above this key tile has nothing to add
-        if (!CAUSAL || kv0 <= wq_hi) {
-            const bool boundary = (kv0 + C::BKV > L) || (CAUSAL && kv0 + C::BKV - 1 > wq_lo);
-            if (boundary)
-                tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
-            else
-                tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
-        }
+        // (every wave takes the masked variant here, also one whose rows see the whole tile: a second
+        // variant in this loop makes the compiler keep two sets of accumulator registers and spill)
+        if (!CAUSAL || kv0 <= wq_hi)
+            tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
         VA_FWD_ITER_END()
     }
 #undef VA_FWD_ITER_BEGIN
