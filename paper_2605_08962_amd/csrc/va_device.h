@@ -176,6 +176,11 @@ struct TileDma {
             if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
         }
     }
+    // Load instruction i of a tile, i known after unrolling (same as issue_one<i>).
+    __device__ __forceinline__ void issue_one_rt(int i, const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
+        const uint32_t off = ragged ? last[i] : full[i];
+        if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+    }
     // One of the NI load instructions of a tile: src = first byte of the tile's first row at this
     // head.  Lets a caller spread a tile's loads over its compute phases: a wave that issues them
     // back to back right after a barrier queues up behind every other wave doing the same and sits

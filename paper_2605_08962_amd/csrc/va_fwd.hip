@@ -35,13 +35,17 @@ constexpr float kRescaleLog2 = 8.0f;
 // BOUNDARY tiles apply the sample-end / causal mask and carry P as bf16 hi + lo: they are where
 // rows with only a handful of keys live (short samples, the first rows under the causal mask),
 // whose outputs are O(1), so a single bf16 rounding of P would eat most of the 1e-2 tolerance.
-template <int D, bool CAUSAL, bool BOUNDARY>
+// `issue` is called with slot numbers 0..3 spread over the step (FIRST_SLOT..3 only, for a caller that
+// has already run the earlier ones): the caller hangs the tile loads of the iterations ahead on
+// them, so that they trickle into the memory pipeline between the MFMAs instead of queueing up
+// behind every other wave's right after the barrier.
+template <int D, bool CAUSAL, bool BOUNDARY, int FIRST_SLOT = 0, typename Issue>
 __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigned char* vb,
                                           const int (&kaddr)[FwdCfg<D>::KS],
                                           const int (&vaddr)[FwdCfg<D>::DB][2],
                                           const bf16x8 (&qf)[FwdCfg<D>::KS],
                                           f32x16 (&oacc)[FwdCfg<D>::DB], float& m, float& lsum,
-                                          float c2, int kv0, int L, int qrow, int hh) {
+                                          float c2, int kv0, int L, int qrow, int hh, Issue& issue) {
     using C = FwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
     f32x16 s[2];
@@ -54,6 +58,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
             bf16x8 a = *(const bf16x8*)(kb + kaddr[ks] + b * 32 * ROWB);
             s[b] = mfma32(a, qf[ks], s[b]);
         }
+        if (FIRST_SLOT <= b) issue(b);
     }
     bool ok[2][16];
 #pragma unroll
@@ -118,8 +123,9 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
             for (int e = 0; e < 8; ++e)
                 plo[b][st][e] = BOUNDARY ? (__bf16)(s[b][8 * st + e] - (float)pb[b][st][e]) : (__bf16)0.f;
         }
+    issue(2);
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db)
+    for (int db = 0; db < C::DB; ++db) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -129,6 +135,8 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
                 oacc[db] = mfma32(a, pb[b][st], oacc[db]);
                 if (BOUNDARY) oacc[db] = mfma32(a, plo[b][st], oacc[db]);
             }
+        if (db == 0) issue(3);
+    }
 }
 
 // A mask-free tile taken on trust: the reference maximum m is NOT looked at, P = exp2(c2 (S - m)) is
@@ -139,12 +147,14 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
 // returns false and the caller repeats the tile with tile_step, which moves m.  This removes the
 // maximum search (one instruction per two scores) from the common path.
 constexpr float kTrustLimit = 1073741824.0f;  // 2^30
-template <int D>
+// (slots 0 and 1 of `issue` have run when it returns false, all four when it returns true)
+template <int D, typename Issue>
 __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, const unsigned char* vb,
                                                    const int (&kaddr)[FwdCfg<D>::KS],
                                                    const int (&vaddr)[FwdCfg<D>::DB][2],
                                                    const bf16x8 (&qf)[FwdCfg<D>::KS],
-                                                   f32x16 (&oacc)[FwdCfg<D>::DB], float m, float& lsum, float c2) {
+                                                   f32x16 (&oacc)[FwdCfg<D>::DB], float m, float& lsum, float c2,
+                                                   Issue& issue) {
     using C = FwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
     f32x16 s[2];
@@ -157,6 +167,7 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
             bf16x8 a = *(const bf16x8*)(kb + kaddr[ks] + b * 32 * ROWB);
             s[b] = mfma32(a, qf[ks], s[b]);
         }
+        issue(b);
     }
     const float mc = m * c2;
     float rs = 0.f;
@@ -169,8 +180,9 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
         }
     if (__builtin_amdgcn_ballot_w64(!(rs <= kTrustLimit)) != 0) return false;  // wave-uniform, rare
     lsum += rs;
+    issue(2);
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db)
+    for (int db = 0; db < C::DB; ++db) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -181,6 +193,8 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
                 bf16x8 a = cat4(lds_read_tr(p0 + vaddr[db][0]), lds_read_tr(p0 + vaddr[db][1]));
                 oacc[db] = mfma32(a, pb, oacc[db]);
             }
+        if (db == 0) issue(3);
+    }
     return true;
 }
 
@@ -235,9 +249,17 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     TileDma<D, C::BKV> dma;  // K and V share the offsets: same shape, same row pitch
     dma.init(row_bytes, L, w, l);
     const uint32_t lds0 = lds_address(lds);
-    auto load_k = [&](int j, int slot) { dma.issue(kbase, row_bytes, j * C::BKV, L, lds0 + slot * C::TILE, w); };
-    auto load_v = [&](int j, int slot) { dma.issue(vbase, row_bytes, j * C::BKV, L, lds0 + (3 + slot) * C::TILE, w); };
-
+    // Staging: K tiles run two iterations ahead in three LDS slots, V tiles one ahead in two.  The
+    // pointers advance by additions; loads are issued unconditionally (past the last tile of this
+    // workgroup the last one is fetched again, into a slot nobody reads any more), so that every
+    // iteration has the same number of loads in flight and nothing branches around them.
+    const int64_t tile_bytes = (int64_t)C::BKV * row_bytes;
+    const bool ragged_sample = (L % C::BKV) != 0;
+    const int last_tile = (L + C::BKV - 1) / C::BKV - 1;  // the tile holding the sample's end
+    auto tile_ptr = [&](const unsigned char* base, int j) { return base + (size_t)min(j, je - 1) * tile_bytes; };
+    auto load_tile = [&](const unsigned char* base, int j, uint32_t lds_tile) {
+        dma.issue_tile(tile_ptr(base, j), ragged_sample && min(j, je - 1) == last_tile, lds_tile, w);
+    };
     // per-lane LDS offsets: K rows read along the row (A operand of S^T), V read down the columns
     int kaddr[C::KS], vaddr[C::DB][2];
 #pragma unroll
@@ -259,9 +281,9 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // prologue: K(0), V(0), K(1) and this lane's Q fragments.  Everything is waited for here, once:
     // the compiler cannot see the direct-to-LDS loads, and if the Q loads were still pending in its
     // bookkeeping at loop entry it would put a wait for ALL outstanding loads into every iteration.
-    load_k(jb, 0);
-    load_v(jb, 0);
-    if (jb + 1 < je) load_k(jb + 1, 1);
+    load_tile(kbase, jb, lds0);
+    load_tile(vbase, jb, lds0 + 3 * C::TILE);
+    load_tile(kbase, jb + 1, lds0 + C::TILE);
     bf16x8 qf[C::KS];
     {
         const __bf16* qp = Q + ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
@@ -277,23 +299,39 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     int kslot = 0;  // (j - jb) % 3
     int vslot = 0;  // (j - jb) % 2
     int j = jb;
-    // Issue the prefetches of iteration j, return the LDS tiles of iteration j.
+    // Iteration j first fixes what it will load (V(j+1) into the other V slot, K(j+2) into the K slot
+    // of tile j-1) and then lets the tile step issue those 2 NI loads in four portions, V first.
+    const unsigned char *iss_v = nullptr, *iss_k = nullptr;
+    uint32_t iss_v_lds = 0, iss_k_lds = 0;
+    bool iss_v_ragged = false, iss_k_ragged = false;
+    auto issue = [&](int slot) {  // slot is a compile-time constant after inlining
+        constexpr int NI = C::NI, HALF = (NI + 1) / 2;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            if (slot == (i < HALF ? 0 : 1)) dma.issue_one_rt(i, iss_v, iss_v_ragged, iss_v_lds, w);
+            if (slot == (i < HALF ? 2 : 3)) dma.issue_one_rt(i, iss_k, iss_k_ragged, iss_k_lds, w);
+        }
+    };
 #define VA_FWD_ITER_BEGIN()                                                                \
         const int kv0 = j * C::BKV;                                                            \
-        if (j + 1 < je) load_v(j + 1, vslot ^ 1);                                              \
-        if (j + 2 < je) load_k(j + 2, kslot == 0 ? 2 : kslot - 1); /* slot (j + 2 - jb) % 3 */ \
+        iss_v = tile_ptr(vbase, j + 1);                                                        \
+        iss_k = tile_ptr(kbase, j + 2);                                                        \
+        iss_v_ragged = ragged_sample && min(j + 1, je - 1) == last_tile;                       \
+        iss_k_ragged = ragged_sample && min(j + 2, je - 1) == last_tile;                       \
+        iss_v_lds = lds0 + (3 + (vslot ^ 1)) * C::TILE;                                        \
+        iss_k_lds = lds0 + (kslot == 0 ? 2 : kslot - 1) * C::TILE; /* slot (j + 2 - jb) % 3 */ \
         const unsigned char* kb = kbuf + kslot * C::TILE;                                      \
         const unsigned char* vb = vbuf + vslot * C::TILE;
     // K(j+1) and V(j+1) must have landed; K(j+2), issued last, may stay in flight.
 #define VA_FWD_ITER_END()                                                                  \
-        if (j + 2 < je) wait_vmcnt<C::NI>(); else wait_vmcnt<0>();                             \
+        wait_vmcnt<C::NI>();                                                                   \
         wg_barrier();                                                                          \
         kslot = kslot == 2 ? 0 : kslot + 1;                                                    \
         vslot ^= 1;
 
     if (j < min(n_plain, je)) {  // the first mask-free tile sets the reference maximum
         VA_FWD_ITER_BEGIN()
-        tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
+        tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
         VA_FWD_ITER_END()
         ++j;
     }
@@ -301,19 +339,27 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
         VA_FWD_ITER_BEGIN()
         // (measured: worth 2 % at head_dim 64 and 80, where the vector ALU is the busier pipe; at 128
         // the matrix pipe is, and the second code path only costs registers)
-        if (D > 96 || !tile_step_trusting<D>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2))
-            tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
+        if constexpr (D > 96) {
+            tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+        } else {
+            if (!tile_step_trusting<D>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, issue))
+                tile_step<D, CAUSAL, false, 2>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+        }
         VA_FWD_ITER_END()
     }
     for (; j < je; ++j) {  // the sample's ragged last tile and the causal diagonal
         VA_FWD_ITER_BEGIN()
-        // causal: a wave whose rows all lie above this key tile has nothing to add
+        // causal: a wave whose rows all lie above this key tile has nothing to add (but still loads).
         // (every wave takes the masked variant here, also one whose rows see the whole tile: a second
         // variant in this loop makes the compiler keep two sets of accumulator registers and spill)
-        if (!CAUSAL || kv0 <= wq_hi)
-            tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh);
+        if (!CAUSAL || kv0 <= wq_hi) {
+            tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+        } else {
+            issue(0); issue(1); issue(2); issue(3);
+        }
         VA_FWD_ITER_END()
     }
+    wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
 #undef VA_FWD_ITER_BEGIN
 #undef VA_FWD_ITER_END
 
