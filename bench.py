@@ -350,6 +350,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    clocks = torch.zeros(6, dtype=torch.int64, device="cuda")
+    binding.profile_clock_probe(clocks)
     binding.profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -357,7 +359,9 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     binding.profile_enable(False)
+    binding.profile_clock_probe(None)
     prof = binding.profile_read()
+    ck = clocks.cpu().tolist()
 
     fwd_flops = w.fwd_flops()
     step_flops = fwd_flops * (3.5 if with_bwd else 1.0)
@@ -384,6 +388,9 @@ def main():
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
     }
+    # average shader clock each compute kernel ran at (cycle counter over the 100 MHz constant clock)
+    out["shader_clock_ghz"] = {n: round(0.1 * ck[2 * i + 1] / ck[2 * i], 3)
+                               for i, n in enumerate(("fwd", "dkdv", "dq")) if ck[2 * i] > 0}
     if with_bwd:
         bwd_ms = sum(kern[n] for n in ("dkdv", "dq")) + prof["delta"][0] / max(prof["delta"][1], 1)
         out["bwd_tflops"] = round(2.5 * fwd_flops / (bwd_ms * 1e-3) / 1e12, 2)

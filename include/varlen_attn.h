@@ -174,6 +174,17 @@ enum {
 int varlen_attn_profile_enable(int on);
 int varlen_attn_profile_read(int kernel, double *total_ms, int64_t *launches);
 
+/*
+ * Shader-clock probe for benchmarks (the chip lowers its clock under matrix-core load, which moves
+ * the attainable fraction of the published peak).  device_counters: DEVICE uint64 [6], 8-byte
+ * aligned, owned and zeroed by the caller, alive until the last launch made while it was set has
+ * finished; NULL (the default) switches the probe off.  While set (process-wide), every workgroup of
+ * the forward, dK/dV and dQ kernels adds its residence time to [0], [2], [4] in ticks of the 100 MHz
+ * constant clock and to [1], [3], [5] in shader cycles: [1]/[0] * 0.1 is the forward's average clock
+ * in GHz.  Two clock reads and two atomics per workgroup; results are unchanged.
+ */
+int varlen_attn_profile_clock_probe(unsigned long long *device_counters);
+
 #ifdef __cplusplus
 }
 #endif

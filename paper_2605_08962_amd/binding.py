@@ -64,6 +64,8 @@ def load():
     lib.varlen_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                              ctypes.POINTER(ctypes.c_int64)]
     lib.varlen_attn_profile_read.restype = ctypes.c_int
+    lib.varlen_attn_profile_clock_probe.argtypes = [vp]
+    lib.varlen_attn_profile_clock_probe.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -175,6 +177,14 @@ def profile_read():
         _check(load().varlen_attn_profile_read(kid, ctypes.byref(ms), ctypes.byref(n)))
         out[name] = (ms.value, n.value)
     return out
+
+
+def profile_clock_probe(counters):
+    """Attach a zeroed int64 device tensor of 6 counters as the shader-clock probe, or None to detach."""
+    if counters is not None and (counters.dtype != torch.int64 or counters.numel() < 6 or not counters.is_cuda
+                                 or not counters.is_contiguous()):
+        raise ValueError("counters must be a contiguous int64 device tensor of at least 6 elements")
+    _check(load().varlen_attn_profile_clock_probe(None if counters is None else counters.data_ptr()))
 
 
 def varlen_attn_merge(o_parts, lse_parts, out=None, lse=None, stream=None):

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
+#include <cstring>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -108,6 +110,76 @@ __global__ void __launch_bounds__(512) split_kernel(float* out, long long* stamp
     }
 }
 
+// Pure MFMA loop on operands read from memory, long enough for the clocks to settle: what the
+// matrix pipe sustains on zero / constant / random bf16 data, and the shader clock it runs at
+// (cycle counter over the 100 MHz real-time counter).  The chip lowers its clock under load.
+__global__ void __launch_bounds__(512)
+sustained_kernel(const bf16x8* __restrict__ in, float* out, unsigned long long* stamps, int iters) {
+    bf16x8 a[4], b[4];
+    for (int i = 0; i < 4; i++) {
+        a[i] = in[(threadIdx.x * 8 + i) % 4096];
+        b[i] = in[(threadIdx.x * 8 + 4 + i) % 4096];
+    }
+    f32x16 c[4];
+    for (int i = 0; i < 4; i++)
+        for (int r = 0; r < 16; r++) c[i][r] = 0.f;
+    const unsigned long long r0 = __builtin_amdgcn_s_memrealtime(), c0 = __builtin_readcyclecounter();
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int m = 0; m < 16; m++)
+            c[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m & 3], b[(m >> 2) & 3], c[m & 3], 0, 0, 0);
+    }
+    const unsigned long long r1 = __builtin_amdgcn_s_memrealtime(), c1 = __builtin_readcyclecounter();
+    float r = 0;
+    for (int i = 0; i < 4; i++) r += c[i][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+    if (threadIdx.x == 0) {
+        stamps[2 * blockIdx.x] = r1 - r0;
+        stamps[2 * blockIdx.x + 1] = c1 - c0;
+    }
+}
+
+static int sustained_mfma(float* out) {
+    bf16x8* in;
+    unsigned long long* stamps;
+    CK(hipMalloc(&in, 4096 * 16));
+    CK(hipMalloc(&stamps, 256 * 16));
+    unsigned short* h = (unsigned short*)malloc(4096 * 16);
+    unsigned long long hs[512];
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    printf("\n| bf16 operands | waves per SIMD | TFLOP/s (256 CUs) | shader clock GHz |\n|---|---|---|---|\n");
+    for (int mode = 0; mode < 3; mode++) {
+        srand(1);
+        for (int i = 0; i < 4096 * 8; i++) {
+            const float v = mode == 0 ? 0.0f : mode == 1 ? 0.5f : ((rand() / (float)RAND_MAX) * 4.f - 2.f);
+            unsigned int u;
+            memcpy(&u, &v, 4);
+            h[i] = (unsigned short)(u >> 16);
+        }
+        CK(hipMemcpy(in, h, 4096 * 16, hipMemcpyHostToDevice));
+        for (int threads = 256; threads <= 512; threads += 256) {
+            const int iters = 200000 / (threads / 256);
+            sustained_kernel<<<256, threads>>>(in, out, stamps, 1000);
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0));
+            sustained_kernel<<<256, threads>>>(in, out, stamps, iters);
+            CK(hipEventRecord(e1));
+            CK(hipDeviceSynchronize());
+            float ms;
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            CK(hipMemcpy(hs, stamps, 256 * 16, hipMemcpyDeviceToHost));
+            double rt = 0, cy = 0;
+            for (int i = 0; i < 256; i++) { rt += (double)hs[2 * i]; cy += (double)hs[2 * i + 1]; }
+            const double flops = 256.0 * (threads / 64) * (double)iters * 16 * 32768.0;
+            printf("| %s | %d | %.0f | %.2f |\n", mode == 0 ? "all zero" : mode == 1 ? "all 0.5" : "uniform random in [-2, 2)",
+                   threads / 256, flops / ms / 1e9, cy / rt / 10.0);
+        }
+    }
+    return 0;
+}
+
 int main() {
     float* out;
     long long* stamps;
@@ -160,5 +232,5 @@ int main() {
                M ? (double)(h[1] - h[0]) / (2 * ITERS) / 16 : 0.0, V ? (double)(h[9] - h[8]) / (2 * ITERS) / 64 : 0.0); \
     }
     RUN2(0, 1, 0) RUN2(0, 0, 1) RUN2(0, 1, 1) RUN2(1, 0, 1) RUN2(1, 1, 1)
-    return 0;
+    return sustained_mfma(out);
 }

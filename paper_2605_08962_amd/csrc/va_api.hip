@@ -23,6 +23,12 @@ struct ProfSample { int kernel; hipEvent_t a, b; };
 std::mutex g_prof_mutex;
 bool g_prof_on = false;
 std::vector<ProfSample> g_prof_samples;
+unsigned long long* g_clock_probe = nullptr;  // device, 6 counters, caller-owned (see the header)
+
+unsigned long long* clock_probe_slot(int pair) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    return g_clock_probe ? g_clock_probe + 2 * pair : nullptr;
+}
 
 struct ProfScope {
     bool on = false;
@@ -184,6 +190,7 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     a.kv_splits = fl.splits;
     a.part_o = (float*)((char*)workspace + fl.part_o_ofs);
     a.part_lse = (float*)((char*)workspace + fl.part_lse_ofs);
+    a.clock_probe = clock_probe_slot(0);
     {
         ProfScope ps(VA_KERNEL_FWD, stream);
         e = va::launch_fwd(a, stream);
@@ -265,6 +272,8 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     a.max_items_q = lay.q.max_items;
     a.total_tokens = p->total_tokens; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
+    a.clock_probe_dkdv = clock_probe_slot(1);
+    a.clock_probe_dq = clock_probe_slot(2);
     {
         ProfScope ps(VA_KERNEL_DELTA, stream);
         e = va::launch_bwd_delta(a, stream);
@@ -323,6 +332,13 @@ int varlen_attn_profile_read(int kernel, double* total_ms, int64_t* launches) {
     }
     *total_ms = sum;
     *launches = n;
+    return VA_OK;
+}
+
+int varlen_attn_profile_clock_probe(unsigned long long* device_counters) {
+    if (((uintptr_t)device_counters & 7u) != 0) return VA_ERR_MISALIGNED;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_clock_probe = device_counters;
     return VA_OK;
 }
 

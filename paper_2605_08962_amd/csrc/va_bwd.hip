@@ -314,7 +314,8 @@ __global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
             const __bf16* __restrict__ dO, const float2* __restrict__ stats,
             __bf16* __restrict__ dK, __bf16* __restrict__ dV, const int32_t* __restrict__ hdr,
-            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale) {
+            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale,
+            unsigned long long* __restrict__ clock_probe) {
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE + C::STAT_BYTES;  // Q tile, dO tile, stats
@@ -324,6 +325,8 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
 
     const int item = blockIdx.x / Hkv;
     if (item >= hdr[0]) return;
+    ClockProbe clk;
+    clk.begin(clock_probe);
     stagger_wave_priority();
     const int c = blockIdx.x % Hkv;
     const int g = Hq / Hkv;
@@ -564,6 +567,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
                 }
             }
     }
+    clk.end(clock_probe);
 }
 
 template <int D>
@@ -575,11 +579,11 @@ static hipError_t launch_dkdv_d(const BwdArgs& a, hipStream_t stream) {
     if (a.causal)
         hipLaunchKernelGGL((dkdv_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
-                           a.num_q_heads, a.num_kv_heads, a.scale);
+                           a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dkdv);
     else
         hipLaunchKernelGGL((dkdv_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
-                           a.num_q_heads, a.num_kv_heads, a.scale);
+                           a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dkdv);
     return hipGetLastError();
 }
 
@@ -692,7 +696,7 @@ __global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
           const __bf16* __restrict__ dO, const float2* __restrict__ stats,
           __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
-          int T, int Hq, int Hkv, float scale) {
+          int T, int Hq, int Hkv, float scale, unsigned long long* __restrict__ clock_probe) {
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
@@ -702,6 +706,8 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 
     const int item = blockIdx.x / Hq;
     if (item >= hdr[0]) return;
+    ClockProbe clk;
+    clk.begin(clock_probe);
     const int hp = blockIdx.x % Hq;
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
@@ -878,6 +884,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
                 }
             }
     }
+    clk.end(clock_probe);
 }
 
 template <int D>
@@ -889,11 +896,11 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     if (a.causal)
         hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
-                           a.num_kv_heads, a.scale);
+                           a.num_kv_heads, a.scale, a.clock_probe_dq);
     else
         hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
-                           a.num_kv_heads, a.scale);
+                           a.num_kv_heads, a.scale, a.clock_probe_dq);
     return hipGetLastError();
 }
 

@@ -128,6 +128,23 @@ __device__ __forceinline__ void stagger_wave_priority() {
     if (slot & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
 }
 
+// Optional clock probe of a compute kernel: when `probe` is not null, every workgroup adds the time
+// it was resident in ticks of the 100 MHz real-time counter to probe[0] and in shader cycles to
+// probe[1].  Their ratio is the shader clock the kernel actually ran at (the chip lowers it under
+// load).  Two scalar clock reads and, for one lane, two atomics per workgroup.
+struct ClockProbe {
+    unsigned long long rt0 = 0, cc0 = 0;
+    __device__ __forceinline__ void begin(const unsigned long long* probe) {
+        if (probe) { rt0 = __builtin_amdgcn_s_memrealtime(); cc0 = __builtin_readcyclecounter(); }
+    }
+    __device__ __forceinline__ void end(unsigned long long* probe) const {
+        if (probe && threadIdx.x == 0) {
+            atomicAdd(&probe[0], (unsigned long long)(__builtin_amdgcn_s_memrealtime() - rt0));
+            atomicAdd(&probe[1], (unsigned long long)(__builtin_readcyclecounter() - cc0));
+        }
+    }
+};
+
 // Index of this wave inside its workgroup, as a value the compiler knows to be wave-uniform.
 __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 

@@ -203,7 +203,7 @@ __global__ void __launch_bounds__(256, (D <= 64 ? 3 : 2))
 fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
            __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale, int S,
-           float* __restrict__ part_o, float* __restrict__ part_lse) {
+           float* __restrict__ part_o, float* __restrict__ part_lse, unsigned long long* __restrict__ clock_probe) {
     using C = FwdCfg<D>;
     using LT = LdsTile<D>;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * C::TILE];  // K x3, then V x2
@@ -215,6 +215,8 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
     const int item = bid / Hq;
     if (item >= hdr[0]) return;
+    ClockProbe clk;
+    clk.begin(clock_probe);
     // Heads: consecutive workgroups walk the kv heads first, so that (with Hkv a multiple of the
     // 8 XCDs) every XCD's L2 only ever sees its own kv heads.
     const int hp = bid % Hq;
@@ -383,6 +385,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
                                                           oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
                 }
             if (hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = row_lse;
+            clk.end(clock_probe);
             return;
         }
         __bf16* op = O + ((size_t)(sb + qrow) * Hq + h) * D;
@@ -400,6 +403,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
             }
         if (hh == 0) LSE[(size_t)h * T + sb + qrow] = row_lse;
     }
+    clk.end(clock_probe);
 }
 
 template <int D>
@@ -409,11 +413,11 @@ static hipError_t launch_d(const FwdArgs& a, hipStream_t stream) {
     if (a.causal)
         hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
                            a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
-                           a.kv_splits, a.part_o, a.part_lse);
+                           a.kv_splits, a.part_o, a.part_lse, a.clock_probe);
     else
         hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
                            a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
-                           a.kv_splits, a.part_o, a.part_lse);
+                           a.kv_splits, a.part_o, a.part_lse, a.clock_probe);
     return hipGetLastError();
 }
 

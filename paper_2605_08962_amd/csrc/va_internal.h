@@ -44,6 +44,7 @@ struct FwdArgs {
     int kv_splits;    // >= 1; > 1: every query tile's keys are split over that many workgroups
     float* part_o;    // kv_splits > 1: fp32 [kv_splits, T, Hq, D] partial outputs
     float* part_lse;  // kv_splits > 1: fp32 [kv_splits, Hq, T]
+    unsigned long long* clock_probe;  // null, or 2 counters (see ClockProbe)
 };
 constexpr int FWD_TILE_Q = 128;
 constexpr int FWD_TILE_KV = 64;
@@ -62,6 +63,7 @@ struct BwdArgs {
     int64_t max_items_q;
     int total_tokens, num_q_heads, num_kv_heads, head_dim, causal;
     float scale;
+    unsigned long long *clock_probe_dkdv, *clock_probe_dq;  // null, or 2 counters each (see ClockProbe)
 };
 constexpr int BWD_TILE_KV = 128;  // rows of K/V one dK/dV workgroup owns
 constexpr int BWD_STEP_Q = 64;    // query rows it stages per step
