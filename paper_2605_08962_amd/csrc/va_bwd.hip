@@ -310,7 +310,7 @@ __device__ __forceinline__ void dkdv_issue_part(bool ragged, const TileDma<D, 64
 }
 
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
+__global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
 dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
             const __bf16* __restrict__ dO, const float2* __restrict__ stats,
             __bf16* __restrict__ dK, __bf16* __restrict__ dV, const int32_t* __restrict__ hdr,
@@ -320,7 +320,9 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE + C::STAT_BYTES;  // Q tile, dO tile, stats
     constexpr int PER = 2 * C::NI + 1;                  // loads per wave per step
-    constexpr int NST = 4;                              // LDS stages
+    // LDS stages: four where two workgroups per CU are out of reach anyway or still fit (head_dim 64),
+    // three at head_dim 80, where the fourth would cost the second workgroup
+    constexpr int NST = D == 80 ? 3 : 4;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int item = blockIdx.x / Hkv;
@@ -412,11 +414,10 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         taddr[db][1] = LT::tr_off(l, 8, db);
     }
 
-    // prologue: three steps in flight plus this lane's K and V fragments; all waited for once (see the
+    // prologue: NST - 1 steps in flight plus this lane's K and V fragments; all waited for once (see the
     // forward kernel for why the register loads must not be left pending at loop entry)
-    issue_all();
-    issue_all();
-    issue_all();
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i) issue_all();
     bf16x8 kf[C::KS], vf[C::KS];
     {
         const size_t off = ((size_t)(sb + (kvalid ? kv : 0)) * Hkv + c) * D + 8 * hh;
@@ -438,10 +439,10 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     const float c2 = scale * kLog2e;
     const int wk_lo = kv0 + 32 * w;
 
-    // Stage protocol.  Step i lives in stage i % 4.  VA_DKDV_SYNC() ends the part of step idx that
-    // reads stage idx - 1: it waits until step idx + 1 has landed (step idx + 2, issued one sync
-    // earlier, may stay in flight), passes the barrier, after which every wave is done with stage
-    // idx - 1, and refills that stage with step idx + 3.
+    // Stage protocol.  Step i lives in stage i % NST.  VA_DKDV_SYNC() ends the part of step idx that
+    // reads stage idx - 1: it waits until step idx + 1 has landed (with four stages step idx + 2,
+    // issued one sync earlier, may stay in flight), passes the barrier, after which every wave is done
+    // with stage idx - 1, and refills that stage with step idx + NST - 1.
     int stage_i = 0;  // stage of the current step ("idx" in the comment above)
 #ifdef VA_PHASE_CLOCKS
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tm[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -449,7 +450,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     unsigned long long nplain = 0;
 #endif
 #define VA_DKDV_SYNC()                                                               \
-        wait_vmcnt<PER>();                                                               \
+        wait_vmcnt<(NST - 3) * PER>();                                                   \
         VA_CLK(1)                                                                        \
         wg_barrier();                                                                    \
         VA_CLK(2)
@@ -692,7 +693,7 @@ __device__ __forceinline__ void dq_run_A(const DqOpsA<D>& f, const bf16x8 (&frag
 }
 
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, (D <= 64 ? 2 : 1))
+__global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
           const __bf16* __restrict__ dO, const float2* __restrict__ stats,
           __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,

@@ -64,7 +64,8 @@ __device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
 // of row r lives in slot c ^ swz(r).  swz is chosen so that (a) 16 consecutive rows read at one
 // logical chunk (MFMA A operand read along the row) and (b) 4 consecutive rows read over one
 // 64-byte span (transposing read down the columns) both cover all 64 banks exactly once.
-// Rows are 128 bytes for head_dim 64 and 256 bytes otherwise (head_dim 80 / 96 leave slots unused).
+// Rows are 128 bytes for head_dim 64 and 256 bytes for 96 (4 slots unused) and 128; head_dim 80 has a
+// packed layout of its own (LdsTile<80>).
 // ------------------------------------------------------------------------------------------------
 #define VA_GLOBAL __attribute__((address_space(1)))
 
@@ -73,7 +74,7 @@ struct LdsTile {
     static constexpr int ROWB = D <= 64 ? 128 : 256;  // bytes per row
     static constexpr int SLOTS = ROWB / 16;
     static constexpr int CHUNKS = D / 8;              // slots that hold data
-    static constexpr int RPI = 1024 / ROWB;           // rows one wave-wide load instruction fills
+    static constexpr int BLOCK_POS = 16 * SLOTS;      // 16-byte positions in a block of 16 rows
     __device__ __forceinline__ static int swz(int r) {
         if (ROWB == 256) return ((r & 3) << 2) | ((r >> 2) & 3);
         const int x = (r >> 1) & 7;
@@ -86,6 +87,51 @@ struct LdsTile {
         const int r = row0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
         const int c = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
         return off(r, c) + 8 * (lane & 1);
+    }
+    // Which (row of the block, logical chunk) lives at 16-byte position p of a 16-row block; false
+    // for a position that holds no data.  The inverse of off(), used to aim the direct-to-LDS loads.
+    __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+        r = p / SLOTS;
+        c = (p % SLOTS) ^ swz(r);
+        return CHUNKS == SLOTS || c < CHUNKS;
+    }
+};
+
+// head_dim 80: 160-byte rows, stored without padding (a 64-row tile takes 10 KB instead of 16 KB, which
+// is what lets three forward and two backward workgroups share a CU).  Ten chunks per row rule out an
+// XOR swizzle, so each block of 16 rows (2560 bytes = 10 segments of 256 bytes = 16 positions) is laid
+// out by hand.  With a = r / 4 and b = r % 4 inside the block, chunk c of row r sits in
+//     segment 2a + c/4  (c < 8)   or   segment c  (c = 8, 9),     position 4b + (c + a) % 4.
+// (a) For one c the 16 rows occupy 16 different positions, so a row-wise 16-byte read of 16 rows covers
+// all 64 banks once.  (b) For one a (4 rows) and one group of 4 chunks the 16 (row, chunk) pairs do too,
+// which is the footprint of half a transposing read.  (c) Chunks 0-3 and 4-7 of a row are adjacent in
+// LDS (rotated), so four lanes of a load still fetch 64 contiguous bytes from memory.
+template <>
+struct LdsTile<80> {
+    static constexpr int ROWB = 160;  // nominal: a block of 16 rows is 16 * ROWB bytes
+    static constexpr int CHUNKS = 10;
+    static constexpr int BLOCK_POS = 160;
+    __device__ __forceinline__ static int pos(int r, int c) {  // r in [0, 16)
+        const int a = r >> 2, b = r & 3;
+        const int seg = c < 8 ? 2 * a + (c >> 2) : c;
+        return 16 * seg + 4 * b + ((c + a) & 3);
+    }
+    __device__ __forceinline__ static int off(int r, int c) { return (r >> 4) * (16 * ROWB) + 16 * pos(r & 15, c); }
+    // Columns 80..95 of the third 32-column block do not exist: the lanes that would address them
+    // re-read chunks 8 and 9 (same addresses as their partner lanes; the results are never used).
+    __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
+        const int r = row0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
+        int c = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        if (c >= CHUNKS) c -= 2;
+        return off(r, c) + 8 * (lane & 1);
+    }
+    __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+        const int seg = p >> 4, b = (p >> 2) & 3, e = p & 3;
+        int a;
+        if (seg < 8) { a = seg >> 1; c = 4 * (seg & 1) + ((e - a) & 3); }
+        else { c = seg; a = (e - c) & 3; }
+        r = 4 * a + b;
+        return true;
     }
 };
 
@@ -156,8 +202,9 @@ __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readf
 template <int D, int ROWS>
 struct TileDma {
     using T = LdsTile<D>;
-    static constexpr int NI = ROWS / T::RPI / 4;  // load instructions per wave per tile
-    static_assert(ROWS % (T::RPI * 4) == 0, "tile rows must split evenly over 4 waves");
+    static_assert(ROWS == 64, "one block of 16 rows per wave");
+    static constexpr int NI = (T::BLOCK_POS + 63) / 64;  // load instructions per wave per tile
+    static constexpr int WAVE_BYTES = 16 * T::ROWB;      // LDS bytes of one wave's 16-row block
     uint32_t full[NI], last[NI];
     bool active[NI];
     // row_bytes: bytes between consecutive rows of the tensor; L: rows in the sample
@@ -165,13 +212,17 @@ struct TileDma {
         const int last_r0 = (L - 1) / ROWS * ROWS;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int blk = wave * NI + i;
-            const int row = blk * T::RPI + lane / T::SLOTS;
-            const int c = (lane % T::SLOTS) ^ T::swz(row);
-            active[i] = T::CHUNKS == T::SLOTS || c < T::CHUNKS;
+            const int p = 64 * i + lane;  // position inside this wave's block
+            int r = 0, c = 0;
+            active[i] = T::locate(p < T::BLOCK_POS ? p : 0, r, c) && p < T::BLOCK_POS;
+            const int row = 16 * wave + r;
             full[i] = (uint32_t)row * row_bytes + c * 16;
             last[i] = (uint32_t)min(row, L - 1 - last_r0) * row_bytes + c * 16;
         }
+    }
+    // LDS byte address of load instruction i of `wave` in the tile at `tile`
+    __device__ __forceinline__ static uint32_t dest(uint32_t tile, int wave, int i) {
+        return tile + wave * WAVE_BYTES + i * 1024;
     }
     // base: first byte of the sample's row 0 at this head; r0: first row of the tile; tile: LDS byte
     // address of the tile; wave: uniform_wave_id()
@@ -182,7 +233,7 @@ struct TileDma {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const uint32_t off = ragged ? last[i] : full[i];
-            if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+            if (active[i]) dma16(src, off, dest(tile, wave, i));
         }
     }
     // All loads of a tile whose first row's bytes at this head start at src.
@@ -190,13 +241,13 @@ struct TileDma {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const uint32_t off = ragged ? last[i] : full[i];
-            if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+            if (active[i]) dma16(src, off, dest(tile, wave, i));
         }
     }
     // Load instruction i of a tile, i known after unrolling (same as issue_one<i>).
     __device__ __forceinline__ void issue_one_rt(int i, const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
         const uint32_t off = ragged ? last[i] : full[i];
-        if (active[i]) dma16(src, off, tile + (wave * NI + i) * 1024);
+        if (active[i]) dma16(src, off, dest(tile, wave, i));
     }
     // One of the NI load instructions of a tile: src = first byte of the tile's first row at this
     // head.  Lets a caller spread a tile's loads over its compute phases: a wave that issues them
@@ -206,7 +257,7 @@ struct TileDma {
     __device__ __forceinline__ void issue_one(const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
         static_assert(I >= 0 && I < NI, "no such load");
         const uint32_t off = ragged ? last[I] : full[I];
-        if (active[I]) dma16(src, off, tile + (wave * NI + I) * 1024);
+        if (active[I]) dma16(src, off, dest(tile, wave, I));
     }
 };
 

@@ -198,8 +198,13 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
     return true;
 }
 
+// Workgroups per CU the kernel is compiled for (registers) and its LDS allows: head_dim 80 fits three
+// only without the causal mask, whose boundary path needs more registers.
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, (D <= 64 ? 3 : 2))
+constexpr int kFwdWgsPerCu = (D <= 64 || (D == 80 && !CAUSAL)) ? 3 : 2;
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
 fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
            __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale, int S,
