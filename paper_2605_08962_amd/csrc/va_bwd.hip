@@ -14,10 +14,20 @@
 //
 // Staging is the forward's: 64-row tiles go straight from HBM/L2 into XOR-swizzled LDS tiles with
 // direct-to-LDS loads, three stages deep, one barrier per step, completion tracked with vmcnt.
+//
+// The file is compiled three times (VA_BWD_PART): part 0 holds everything but the head_dim 128 dK/dV
+// and dQ kernels, which parts 1 and 2 build under a different instruction-scheduling strategy of the
+// compiler (measured 7 % and 4 % faster there, slower for the other head sizes).
 #include "va_device.h"
 #include "va_internal.h"
 
+#ifndef VA_BWD_PART
+#define VA_BWD_PART 0
+#endif
+
 namespace va {
+hipError_t launch_dkdv_128(const BwdArgs& a, hipStream_t stream);  // part 1
+hipError_t launch_dq_128(const BwdArgs& a, hipStream_t stream);    // part 2
 
 #ifdef VA_PHASE_CLOCKS
 __device__ unsigned long long g_phase[16];
@@ -58,6 +68,7 @@ stats_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const 
     }
 }
 
+#if VA_BWD_PART == 0
 hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream) {
     const int64_t rows = (int64_t)a.total_tokens * a.num_q_heads;
     dim3 grid((unsigned)((rows + 15) / 16)), block(256);
@@ -72,6 +83,8 @@ hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream) {
     }
     return hipGetLastError();
 }
+
+#endif  // part 0
 
 template <int D>
 struct BwdCfg {
@@ -588,15 +601,19 @@ static hipError_t launch_dkdv_d(const BwdArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+#if VA_BWD_PART == 0
 hipError_t launch_bwd_dkdv(const BwdArgs& a, hipStream_t stream) {
     switch (a.head_dim) {
         case 64: return launch_dkdv_d<64>(a, stream);
         case 80: return launch_dkdv_d<80>(a, stream);
         case 96: return launch_dkdv_d<96>(a, stream);
-        case 128: return launch_dkdv_d<128>(a, stream);
+        case 128: return launch_dkdv_128(a, stream);
         default: return hipErrorInvalidValue;
     }
 }
+#elif VA_BWD_PART == 1
+hipError_t launch_dkdv_128(const BwdArgs& a, hipStream_t stream) { return launch_dkdv_d<128>(a, stream); }
+#endif
 
 // ------------------------------------------------------------------------------------------------
 // dQ
@@ -905,15 +922,19 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+#if VA_BWD_PART == 2
+hipError_t launch_dq_128(const BwdArgs& a, hipStream_t stream) { return launch_dq_d<128>(a, stream); }
+#elif VA_BWD_PART == 0
 hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream) {
     switch (a.head_dim) {
         case 64: return launch_dq_d<64>(a, stream);
         case 80: return launch_dq_d<80>(a, stream);
         case 96: return launch_dq_d<96>(a, stream);
-        case 128: return launch_dq_d<128>(a, stream);
+        case 128: return launch_dq_128(a, stream);
         default: return hipErrorInvalidValue;
     }
 }
+#endif
 
 #ifdef VA_PHASE_CLOCKS
 extern "C" int varlen_attn_debug_phase(unsigned long long* out, int reset) {
