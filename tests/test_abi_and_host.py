@@ -130,3 +130,8 @@ def test_bf16_rounding_matches_torch():
     ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(bits, ref)
     assert np.array_equal(W.bf16_bits_to_f32(bits), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+
+
+def test_clock_probe_rejects_a_misaligned_pointer(lib):
+    assert lib.varlen_attn_profile_clock_probe(ctypes.c_void_p(12)) == 7
+    assert lib.varlen_attn_profile_clock_probe(None) == 0

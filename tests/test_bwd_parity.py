@@ -106,3 +106,33 @@ def test_deterministic():
     a = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], True, w.scale)
     b = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], True, w.scale)
     assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def test_clock_probe_counts_and_leaves_results_alone():
+    # While a probe is attached, every workgroup of the three compute kernels adds its residence time
+    # in constant-clock ticks and in shader cycles; outputs must be bit-identical with and without it.
+    from paper_2605_08962_amd import binding
+    w = W.make_custom([700, 130, 64], 4, 2, 64, True, seed=31, with_dout=True)
+    d = upload(w)
+    def run():
+        o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], w.causal, w.scale, kv_splits=1)
+        g = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], w.causal, w.scale)
+        torch.cuda.synchronize()
+        return (o, lse) + tuple(g)
+    ref = run()
+    clocks = torch.zeros(6, dtype=torch.int64, device="cuda")
+    binding.profile_clock_probe(clocks)
+    try:
+        got = run()
+    finally:
+        binding.profile_clock_probe(None)
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+    c = clocks.cpu().tolist()
+    for i in range(3):
+        ticks, cycles = c[2 * i], c[2 * i + 1]
+        assert ticks > 0 and cycles > 0
+        assert 0.5 <= 0.1 * cycles / ticks <= 2.6, f"kernel {i}: {0.1 * cycles / ticks} GHz"
+    after = clocks.clone()
+    run()  # detached: the counters must not move any more
+    assert torch.equal(after, clocks)
