@@ -463,7 +463,7 @@ def main():
     out["shader_clock_ghz"] = {n: round(0.1 * ck[2 * i + 1] / ck[2 * i], 3)
                                for i, n in enumerate(("fwd", "dkdv", "dq")) if ck[2 * i] > 0}
     if with_bwd:
-        bwd_ms = sum(kern[n] for n in ("dkdv", "dq")) + prof["delta"][0] / max(prof["delta"][1], 1)
+        bwd_ms = sum(kern[n] for n in ("dkdv", "dq"))
         out["bwd_tflops"] = round(2.5 * fwd_flops / (bwd_ms * 1e-3) / 1e12, 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -166,9 +166,9 @@ int varlen_attn_balance_partition(const int32_t *lengths, int32_t num_seqs, int3
 enum {
     VA_KERNEL_SCHED = 0, /* tile scheduler (1 launch per forward, 2 per backward) */
     VA_KERNEL_FWD = 1,   /* forward attention */
-    VA_KERNEL_DELTA = 2, /* backward: Delta = rowsum(dO * O) */
+    VA_KERNEL_DELTA = 2, /* unused (kept for numbering): Delta = rowsum(dO * O) is computed inside the dQ kernel */
     VA_KERNEL_DKDV = 3,  /* backward: dK, dV */
-    VA_KERNEL_DQ = 4,    /* backward: dQ */
+    VA_KERNEL_DQ = 4,    /* backward: dQ (also writes the per-row statistics dK/dV reads; launched first) */
     VA_KERNEL_MERGE = 5  /* merge of partial results (varlen_attn_merge, split forward) */
 };
 int varlen_attn_profile_enable(int on);

@@ -274,19 +274,15 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     a.head_dim = p->head_dim; a.causal = p->causal; a.scale = p->softmax_scale;
     a.clock_probe_dkdv = clock_probe_slot(1);
     a.clock_probe_dq = clock_probe_slot(2);
+    // dQ first: it also writes the row statistics {LSE * log2 e, -Delta} that dK/dV reads
     {
-        ProfScope ps(VA_KERNEL_DELTA, stream);
-        e = va::launch_bwd_delta(a, stream);
+        ProfScope ps(VA_KERNEL_DQ, stream);
+        e = va::launch_bwd_dq(a, stream);
     }
     if (e != hipSuccess) return hip_fail(e);
     {
         ProfScope ps(VA_KERNEL_DKDV, stream);
         e = va::launch_bwd_dkdv(a, stream);
-    }
-    if (e != hipSuccess) return hip_fail(e);
-    {
-        ProfScope ps(VA_KERNEL_DQ, stream);
-        e = va::launch_bwd_dq(a, stream);
     }
     if (e != hipSuccess) return hip_fail(e);
     return VA_OK;

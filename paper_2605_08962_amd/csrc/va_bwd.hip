@@ -1,7 +1,10 @@
 // Backward kernels.  P is recomputed from Q, K and the saved LSE (the paper recomputes core
 // attention in the backward pass, Section 5 "Selective Activation Offloading").
 //
-//   stats  : per (head, row): LSE * log2(e) and -Delta = -sum_d dO * O      (HBM-bound sweep)
+//   (row statistics: per (head, row) LSE * log2(e) and -Delta = -sum_d dO * O; every dQ workgroup
+//    computes them for its own 128 rows while it loads its fragments and writes them to the workspace,
+//    where the dK/dV kernel, launched after it, finds them.  Delta is stored negated so that the dK/dV
+//    kernel can load it straight into the accumulator of dP = dO V^T and get dP - Delta for free.)
 //   dkdv   : one workgroup per (128-row key tile, kv head); loops over the query heads of the
 //            group and over 64-row query steps; S = Q K^T is kept with one KEY per lane, so
 //            that P and dS are directly the B operands of dV^T += dO^T P and dK^T += Q^T dS
@@ -39,52 +42,6 @@ __device__ unsigned long long g_phase[16];
 #define VA_CLK(i)
 #define VA_CLK_ACCUM(n)
 #endif
-
-// ------------------------------------------------------------------------------------------------
-// stats[h][i] = { LSE[h][i] * log2(e), -sum_d dO[i,h,d] * O[i,h,d] }
-// (Delta is stored negated so that the dK/dV kernel can load it straight into the accumulator of
-// dP = dO V^T and get dP - Delta out of the MFMA for free.)
-// ------------------------------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(256)
-stats_kernel(const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
-             float2* __restrict__ stats, int T, int Hq) {
-    // 16 lanes per (token, head) row, one 16-byte chunk each
-    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int c = threadIdx.x & 15;
-    const int64_t rows = (int64_t)T * Hq;
-    float acc = 0.f;
-    if (row < rows && c < D / 8) {
-        bf16x8 a = *(const bf16x8*)(dO + row * D + c * 8);
-        bf16x8 b = *(const bf16x8*)(O + row * D + c * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
-    }
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 16);
-    if (row < rows && c == 0) {
-        const int64_t i = row / Hq, h = row % Hq;
-        stats[h * T + i] = make_float2(LSE[h * T + i] * kLog2e, -acc);
-    }
-}
-
-#if VA_BWD_PART == 0
-hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream) {
-    const int64_t rows = (int64_t)a.total_tokens * a.num_q_heads;
-    dim3 grid((unsigned)((rows + 15) / 16)), block(256);
-    auto dO = (const __bf16*)a.dout; auto O = (const __bf16*)a.o;
-    auto st = (float2*)a.stats;
-    switch (a.head_dim) {
-        case 64: hipLaunchKernelGGL(stats_kernel<64>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
-        case 80: hipLaunchKernelGGL(stats_kernel<80>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
-        case 96: hipLaunchKernelGGL(stats_kernel<96>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
-        case 128: hipLaunchKernelGGL(stats_kernel<128>, grid, block, 0, stream, dO, O, a.lse, st, a.total_tokens, a.num_q_heads); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-#endif  // part 0
 
 template <int D>
 struct BwdCfg {
@@ -712,8 +669,8 @@ __device__ __forceinline__ void dq_run_A(const DqOpsA<D>& f, const bf16x8 (&frag
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
-          const __bf16* __restrict__ dO, const float2* __restrict__ stats,
-          __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
+          const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
+          float2* __restrict__ stats, __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
           int T, int Hq, int Hkv, float scale, unsigned long long* __restrict__ clock_probe) {
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
@@ -796,10 +753,20 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
             qf[ks] = qvalid ? *(const bf16x8*)(Q + off + 16 * ks) : z;
             dof[ks] = qvalid ? *(const bf16x8*)(dO + off + 16 * ks) : z;
         }
+        // Row statistics of this lane's row: Delta = sum_d dO * O (each half of the wave sums its 8 of
+        // every 16 columns), and the saved LSE in base 2.  Written out for the dK/dV kernel.
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            bf16x8 z = {};
+            const bf16x8 of = qvalid ? *(const bf16x8*)(O + off + 16 * ks) : z;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)dof[ks][e], (float)of[e], part);
+        }
+        ndelta = -xhalf_sum(part);
         if (qvalid) {
-            const float2 st = stats[(size_t)h * T + sb + qrow];
-            lse2 = st.x;
-            ndelta = st.y;
+            lse2 = LSE[(size_t)h * T + sb + qrow] * kLog2e;
+            if (hh == 0) stats[(size_t)h * T + sb + qrow] = make_float2(lse2, ndelta);
         }
     }
     wait_vmcnt<0>();
@@ -910,13 +877,14 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(a.max_items_q * a.num_q_heads)), block(256);
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
     auto dO = (const __bf16*)a.dout;
-    auto st = (const float2*)a.stats;
+    auto o = (const __bf16*)a.o;
+    auto st = (float2*)a.stats;
     if (a.causal)
-        hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
+        hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale, a.clock_probe_dq);
     else
-        hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
+        hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
                            (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale, a.clock_probe_dq);
     return hipGetLastError();

@@ -73,7 +73,6 @@ constexpr int BWD_STEP_KV = 64;   // key rows it stages per step
 hipError_t launch_merge(const void* o_parts, bool parts_fp32, const float* lse_parts, int P, int T, int H, int D,
                         void* o, float* lse, hipStream_t stream);
 
-hipError_t launch_bwd_delta(const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream);
 
