@@ -284,7 +284,7 @@ __global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
 dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
             const __bf16* __restrict__ dO, const float2* __restrict__ stats,
             __bf16* __restrict__ dK, __bf16* __restrict__ dV, const int32_t* __restrict__ hdr,
-            const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale,
+            const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale,
             unsigned long long* __restrict__ clock_probe) {
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
@@ -295,12 +295,12 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     constexpr int NST = D == 80 ? 3 : 4;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
-    const int item = blockIdx.x / Hkv;
+    int item, c;  // work item and kv head (see xcd_item_head)
+    xcd_item_head(blockIdx.x, max_items, Hkv, item, c);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);
     stagger_wave_priority();
-    const int c = blockIdx.x % Hkv;
     const int g = Hq / Hkv;
     const WorkItem it = items[item];
     // same for the whole workgroup: tell the compiler, so that everything derived stays in SGPRs
@@ -549,11 +549,11 @@ static hipError_t launch_dkdv_d(const BwdArgs& a, hipStream_t stream) {
     auto st = (const float2*)a.stats;
     if (a.causal)
         hipLaunchKernelGGL((dkdv_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, st,
-                           (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
+                           (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, (int)a.max_items_kv, a.total_tokens,
                            a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dkdv);
     else
         hipLaunchKernelGGL((dkdv_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, st,
-                           (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, a.total_tokens,
+                           (__bf16*)a.dk, (__bf16*)a.dv, a.sched_hdr_kv, a.items_kv, (int)a.max_items_kv, a.total_tokens,
                            a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dkdv);
     return hipGetLastError();
 }
@@ -671,7 +671,7 @@ __global__ void __launch_bounds__(256, (D <= 80 ? 2 : 1))
 dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
           const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
           float2* __restrict__ stats, __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
-          int T, int Hq, int Hkv, float scale, unsigned long long* __restrict__ clock_probe) {
+          int max_items, int T, int Hq, int Hkv, float scale, unsigned long long* __restrict__ clock_probe) {
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
@@ -679,11 +679,11 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     constexpr int PER = 2 * C::NI;      // loads per wave per step
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
-    const int item = blockIdx.x / Hq;
+    int item, hp;
+    xcd_item_head(blockIdx.x, max_items, Hq, item, hp);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);
-    const int hp = blockIdx.x % Hq;
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
@@ -881,11 +881,11 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     auto st = (float2*)a.stats;
     if (a.causal)
         hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
-                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
+                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale, a.clock_probe_dq);
     else
         hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
-                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, a.total_tokens, a.num_q_heads,
+                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens, a.num_q_heads,
                            a.num_kv_heads, a.scale, a.clock_probe_dq);
     return hipGetLastError();
 }

@@ -191,6 +191,28 @@ struct ClockProbe {
     }
 };
 
+// Workgroup id -> (work item, head slot) for a launch of n_items x heads workgroups.  Workgroup ids are
+// dealt round-robin to the 8 XCDs, each with an L2 of its own.  With heads a multiple of 8, XCD x gets
+// the head slots x, x + 8, ...; it walks the (cost-sorted) work list in chunks of kXcdChunk items and
+// finishes a chunk for one of its heads before it takes the chunk for the next, so that the workgroups
+// running together on an XCD stream the K/V (or Q/dO) of ONE head where they used to interleave all of
+// the XCD's heads: the same bytes are shared by more workgroups and stay in L2 for longer.
+constexpr int kXcdChunk = 128;
+__device__ __forceinline__ void xcd_item_head(unsigned bid, int n_items, int heads, int& item, int& hp) {
+    if (heads % 8 != 0) { item = (int)(bid / (unsigned)heads); hp = (int)(bid % (unsigned)heads); return; }
+    const unsigned hx = (unsigned)heads / 8, x = bid % 8, k = bid / 8;  // k-th workgroup of XCD x
+    const unsigned full = (unsigned)n_items / kXcdChunk * kXcdChunk;      // items in whole chunks
+    if (k < full * hx) {
+        const unsigned c = k / (kXcdChunk * hx), rem = k % (kXcdChunk * hx);
+        item = (int)(c * kXcdChunk + rem % kXcdChunk);
+        hp = (int)(x + 8 * (rem / kXcdChunk));
+    } else {
+        const unsigned kk = k - full * hx, r = (unsigned)n_items - full;
+        item = (int)(full + kk % r);
+        hp = (int)(x + 8 * (kk / r));
+    }
+}
+
 // Index of this wave inside its workgroup, as a value the compiler knows to be wave-uniform.
 __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 

@@ -207,7 +207,7 @@ template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
 fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
            __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
-           const WorkItem* __restrict__ items, int T, int Hq, int Hkv, float scale, int S,
+           const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale, int S,
            float* __restrict__ part_o, float* __restrict__ part_lse, unsigned long long* __restrict__ clock_probe) {
     using C = FwdCfg<D>;
     using LT = LdsTile<D>;
@@ -218,13 +218,13 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // for launches too small to fill the chip (few heads, one mid-length sample).
     const int ch = S > 1 ? (int)(blockIdx.x % S) : 0;
     const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
-    const int item = bid / Hq;
+    int item, hp;
+    xcd_item_head(bid, max_items, Hq, item, hp);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);
-    // Heads: consecutive workgroups walk the kv heads first, so that (with Hkv a multiple of the
-    // 8 XCDs) every XCD's L2 only ever sees its own kv heads.
-    const int hp = bid % Hq;
+    // Head slots count the kv heads first, so that (with Hkv a multiple of the 8 XCDs) every XCD's L2
+    // only ever sees its own kv heads.
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
@@ -417,11 +417,11 @@ static hipError_t launch_d(const FwdArgs& a, hipStream_t stream) {
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
     if (a.causal)
         hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
-                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
+                           a.sched_hdr, a.items, (int)a.max_items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
                            a.kv_splits, a.part_o, a.part_lse, a.clock_probe);
     else
         hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
-                           a.sched_hdr, a.items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
+                           a.sched_hdr, a.items, (int)a.max_items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,
                            a.kv_splits, a.part_o, a.part_lse, a.clock_probe);
     return hipGetLastError();
 }
