@@ -58,6 +58,7 @@ __device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
 
 // ------------------------------------------------------------------------------------------------
 // LDS tiles filled by direct-to-LDS loads (global_load_lds_dwordx4).
+// (The layout functions are host-callable as well: a CPU test checks their bank properties.)
 //
 // Such a load writes the 64 lanes' 16-byte chunks to 1024 CONTIGUOUS LDS bytes, so rows cannot be
 // padded against bank conflicts.  Instead the 16-byte chunks of a row are permuted: logical chunk c
@@ -75,22 +76,22 @@ struct LdsTile {
     static constexpr int SLOTS = ROWB / 16;
     static constexpr int CHUNKS = D / 8;              // slots that hold data
     static constexpr int BLOCK_POS = 16 * SLOTS;      // 16-byte positions in a block of 16 rows
-    __device__ __forceinline__ static int swz(int r) {
+    __host__ __device__ __forceinline__ static int swz(int r) {
         if (ROWB == 256) return ((r & 3) << 2) | ((r >> 2) & 3);
         const int x = (r >> 1) & 7;
         return ((x & 1) << 2) | (x >> 1);
     }
-    __device__ __forceinline__ static int off(int r, int c) { return r * ROWB + ((c ^ swz(r)) << 4); }
+    __host__ __device__ __forceinline__ static int off(int r, int c) { return r * ROWB + ((c ^ swz(r)) << 4); }
     // Byte offset this lane passes to lds_read_tr for the 4 x 16 block at rows row0.., columns
     // 32*db + (0 or 16).. of the tile; row0 must be a multiple of 8 (see tr_lane_offset).
-    __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
+    __host__ __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
         const int r = row0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
         const int c = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
         return off(r, c) + 8 * (lane & 1);
     }
     // Which (row of the block, logical chunk) lives at 16-byte position p of a 16-row block; false
     // for a position that holds no data.  The inverse of off(), used to aim the direct-to-LDS loads.
-    __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+    __host__ __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
         r = p / SLOTS;
         c = (p % SLOTS) ^ swz(r);
         return CHUNKS == SLOTS || c < CHUNKS;
@@ -111,21 +112,21 @@ struct LdsTile<80> {
     static constexpr int ROWB = 160;  // nominal: a block of 16 rows is 16 * ROWB bytes
     static constexpr int CHUNKS = 10;
     static constexpr int BLOCK_POS = 160;
-    __device__ __forceinline__ static int pos(int r, int c) {  // r in [0, 16)
+    __host__ __device__ __forceinline__ static int pos(int r, int c) {  // r in [0, 16)
         const int a = r >> 2, b = r & 3;
         const int seg = c < 8 ? 2 * a + (c >> 2) : c;
         return 16 * seg + 4 * b + ((c + a) & 3);
     }
-    __device__ __forceinline__ static int off(int r, int c) { return (r >> 4) * (16 * ROWB) + 16 * pos(r & 15, c); }
+    __host__ __device__ __forceinline__ static int off(int r, int c) { return (r >> 4) * (16 * ROWB) + 16 * pos(r & 15, c); }
     // Columns 80..95 of the third 32-column block do not exist: the lanes that would address them
     // re-read chunks 8 and 9 (same addresses as their partner lanes; the results are never used).
-    __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
+    __host__ __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
         const int r = row0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
         int c = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
         if (c >= CHUNKS) c -= 2;
         return off(r, c) + 8 * (lane & 1);
     }
-    __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+    __host__ __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
         const int seg = p >> 4, b = (p >> 2) & 3, e = p & 3;
         int a;
         if (seg < 8) { a = seg >> 1; c = 4 * (seg & 1) + ((e - a) & 3); }

@@ -135,3 +135,18 @@ def test_bf16_rounding_matches_torch():
 def test_clock_probe_rejects_a_misaligned_pointer(lib):
     assert lib.varlen_attn_profile_clock_probe(ctypes.c_void_p(12)) == 7
     assert lib.varlen_attn_profile_clock_probe(None) == 0
+
+
+def test_lds_tile_layouts_are_consistent_and_bank_conflict_free(tmp_path):
+    # compiles tests/lds_layout_check.hip (host code only runs) against csrc/va_device.h: every
+    # head_dim's layout is a bijection whose row-wise and transposing reads cover the banks once
+    import shutil
+    import subprocess
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not on PATH")
+    exe = tmp_path / "lds_layout_check"
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lds_layout_check.hip")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-O1", "-std=c++17", src, "-o", str(exe)], check=True,
+                   capture_output=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and "lds layouts ok" in r.stdout, r.stdout[-2000:]
