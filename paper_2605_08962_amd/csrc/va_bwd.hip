@@ -296,7 +296,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     int item, c;  // work item and kv head (see xcd_item_head)
-    xcd_item_head(blockIdx.x, max_items, Hkv, item, c);
+    xcd_item_head(blockIdx.x, max_items, Hkv, Hkv, item, c);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);
@@ -680,7 +680,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     int item, hp;
-    xcd_item_head(blockIdx.x, max_items, Hq, item, hp);
+    xcd_item_head(blockIdx.x, max_items, Hq, Hkv, item, hp);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);

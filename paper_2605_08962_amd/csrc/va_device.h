@@ -192,26 +192,35 @@ struct ClockProbe {
     }
 };
 
-// Workgroup id -> (work item, head slot) for a launch of n_items x heads workgroups.  Workgroup ids are
-// dealt round-robin to the 8 XCDs, each with an L2 of its own.  With heads a multiple of 8, XCD x gets
-// the head slots x, x + 8, ...; it walks the (cost-sorted) work list in chunks of kXcdChunk items and
-// finishes a chunk for one of its heads before it takes the chunk for the next, so that the workgroups
-// running together on an XCD stream the K/V (or Q/dO) of ONE head where they used to interleave all of
-// the XCD's heads: the same bytes are shared by more workgroups and stay in L2 for longer.
+// Workgroup id -> (work item, head slot) for a launch of n_items x heads workgroups; head slot hp stands
+// for kv head hp % kv_heads and member hp / kv_heads of its group of query heads.  Workgroup ids are
+// dealt round-robin to the 8 XCDs, each with an L2 of its own.  With kv_heads a multiple of 8, XCD x
+// gets the kv heads x, x + 8, ... and all their query heads.  It walks the (cost-sorted) work list in
+// chunks of kXcdChunk items and finishes a chunk for one kv head (all query heads of the group side by
+// side: they read the same K/V) before it takes the chunk for its next kv head.  The workgroups running
+// together on an XCD thus stream the K/V (or Q/dO) of ONE kv head where a plain item-major order
+// interleaves all of the XCD's heads: the same bytes serve more workgroups and stay in L2 for longer.
 constexpr int kXcdChunk = 128;
-__device__ __forceinline__ void xcd_item_head(unsigned bid, int n_items, int heads, int& item, int& hp) {
-    if (heads % 8 != 0) { item = (int)(bid / (unsigned)heads); hp = (int)(bid % (unsigned)heads); return; }
-    const unsigned hx = (unsigned)heads / 8, x = bid % 8, k = bid / 8;  // k-th workgroup of XCD x
-    const unsigned full = (unsigned)n_items / kXcdChunk * kXcdChunk;      // items in whole chunks
-    if (k < full * hx) {
-        const unsigned c = k / (kXcdChunk * hx), rem = k % (kXcdChunk * hx);
-        item = (int)(c * kXcdChunk + rem % kXcdChunk);
-        hp = (int)(x + 8 * (rem / kXcdChunk));
+__host__ __device__ __forceinline__ void xcd_item_head(unsigned bid, int n_items, int heads, int kv_heads, int& item, int& hp) {
+    if (kv_heads % 8 != 0) { item = (int)(bid / (unsigned)heads); hp = (int)(bid % (unsigned)heads); return; }
+    const unsigned g = (unsigned)(heads / kv_heads), kx = (unsigned)kv_heads / 8;
+    const unsigned x = bid % 8, k = bid / 8;                          // k-th workgroup of XCD x
+    const unsigned full = (unsigned)n_items / kXcdChunk * kXcdChunk;  // items in whole chunks
+    const unsigned per_chunk = kXcdChunk * g;                         // workgroups of one (chunk, kv head)
+    unsigned kvslot, i, gq;
+    if (k < full * g * kx) {
+        const unsigned c = k / (per_chunk * kx), rem = k % (per_chunk * kx);
+        kvslot = rem / per_chunk;
+        i = c * kXcdChunk + (rem % per_chunk) / g;
+        gq = rem % g;
     } else {
-        const unsigned kk = k - full * hx, r = (unsigned)n_items - full;
-        item = (int)(full + kk % r);
-        hp = (int)(x + 8 * (kk / r));
+        const unsigned kk = k - full * g * kx, r = (unsigned)n_items - full;
+        kvslot = kk / (r * g);
+        i = full + (kk % (r * g)) / g;
+        gq = kk % g;
     }
+    item = (int)i;
+    hp = (int)(x + 8 * kvslot + (unsigned)kv_heads * gq);
 }
 
 // Index of this wave inside its workgroup, as a value the compiler knows to be wave-uniform.

@@ -219,7 +219,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const int ch = S > 1 ? (int)(blockIdx.x % S) : 0;
     const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
     int item, hp;
-    xcd_item_head(bid, max_items, Hq, item, hp);
+    xcd_item_head(bid, max_items, Hq, Hkv, item, hp);
     if (item >= hdr[0]) return;
     ClockProbe clk;
     clk.begin(clock_probe);

@@ -5,6 +5,7 @@
 //   2. a row-wise 16-byte read of 16 consecutive rows at one chunk touches each of the 64 banks once;
 //   3. each half (32 lanes) of a transposing read touches no bank with two different addresses;
 //   4. off(r + 16, c) = off(r, c) + 16 * ROWB, which the kernels rely on when they add row-block offsets.
+// It also checks that the workgroup-id -> (work item, head) map of the kernels hits every pair exactly once.
 #include <cstdio>
 #include <map>
 #include <set>
@@ -51,8 +52,26 @@ static int check() {
     return bad;
 }
 
+static int check_work_order() {
+    const int shapes[][3] = {{908, 16, 16}, {1, 16, 16}, {128, 32, 8}, {300, 32, 8}, {257, 8, 8}, {129, 64, 16},
+                             {5, 6, 3}, {1000, 24, 8}, {127, 16, 16}, {256, 8, 8}};
+    int bad = 0;
+    for (auto& sh : shapes) {
+        const int n = sh[0], heads = sh[1], kv = sh[2];
+        std::set<std::pair<int, int>> seen;
+        for (unsigned bid = 0; bid < (unsigned)(n * heads); ++bid) {
+            int item, hp;
+            va::xcd_item_head(bid, n, heads, kv, item, hp);
+            if (item < 0 || item >= n || hp < 0 || hp >= heads || !seen.insert({item, hp}).second) ++bad;
+            if (kv % 8 == 0 && (hp % kv) % 8 != (int)(bid % 8)) ++bad;  // the kv head stays on its XCD
+        }
+        if (bad) std::printf("work order n=%d heads=%d kv=%d: %d errors\n", n, heads, kv, bad);
+    }
+    return bad;
+}
+
 int main() {
-    const int bad = check<64>() + check<80>() + check<96>() + check<128>();
+    const int bad = check<64>() + check<80>() + check<96>() + check<128>() + check_work_order();
     std::printf(bad ? "FAILED: %d\n" : "lds layouts ok\n", bad);
     return bad != 0;
 }
