@@ -20,7 +20,8 @@
 //
 // The file is compiled three times (VA_BWD_PART): part 0 holds everything but the head_dim 128 dK/dV
 // and dQ kernels, which parts 1 and 2 build under a different instruction-scheduling strategy of the
-// compiler (measured 7 % and 4 % faster there, slower for the other head sizes).
+// compiler (measured 7 % and 4 % faster there, slower for the other head sizes; part 1 also with MFMA
+// results in ordinary vector registers, see build.py).
 #include "va_device.h"
 #include "va_internal.h"
 
@@ -33,7 +34,7 @@ hipError_t launch_dkdv_128(const BwdArgs& a, hipStream_t stream);  // part 1
 hipError_t launch_dq_128(const BwdArgs& a, hipStream_t stream);    // part 2
 
 #ifdef VA_PHASE_CLOCKS
-__device__ unsigned long long g_phase[16];
+static __device__ unsigned long long g_phase[16];
 // Time stamps are only taken (scalar memory clock reads) where VA_CLK stands and are consumed by
 // VA_CLK_ACCUM once per step, so that waiting for them does not serialise the phases they separate.
 #define VA_CLK(i) tm[i] = __builtin_readcyclecounter();
@@ -298,8 +299,8 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     int item, c;  // work item and kv head (see xcd_item_head)
     xcd_item_head(blockIdx.x, max_items, Hkv, Hkv, item, c);
     if (item >= hdr[0]) return;
-    ClockProbe clk;
-    clk.begin(clock_probe);
+    ClockProbe wg_clock;
+    wg_clock.begin(clock_probe);
     stagger_wave_priority();
     const int g = Hq / Hkv;
     const WorkItem it = items[item];
@@ -400,6 +401,10 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     }
     wait_vmcnt<0>();
     wg_barrier();
+    if constexpr (D > 80) {  // one wave per SIMD: see park_in_acc_registers
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) { park_in_acc_registers(kf[ks]); park_in_acc_registers(vf[ks]); }
+    }
 
     f32x16 dkacc[C::DB], dvacc[C::DB];
 #pragma unroll
@@ -538,7 +543,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
                 }
             }
     }
-    clk.end(clock_probe);
+    wg_clock.end(clock_probe);
 }
 
 template <int D>
@@ -682,8 +687,8 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     int item, hp;
     xcd_item_head(blockIdx.x, max_items, Hq, Hkv, item, hp);
     if (item >= hdr[0]) return;
-    ClockProbe clk;
-    clk.begin(clock_probe);
+    ClockProbe wg_clock;
+    wg_clock.begin(clock_probe);
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
     const WorkItem it = items[item];
@@ -771,6 +776,10 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     }
     wait_vmcnt<0>();
     wg_barrier();
+    if constexpr (D > 80) {  // one wave per SIMD: see park_in_acc_registers
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) { park_in_acc_registers(qf[ks]); park_in_acc_registers(dof[ks]); }
+    }
 
     f32x16 dqacc[C::DB];
 #pragma unroll
@@ -869,7 +878,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
                 }
             }
     }
-    clk.end(clock_probe);
+    wg_clock.end(clock_probe);
 }
 
 template <int D>
@@ -904,7 +913,7 @@ hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream) {
 }
 #endif
 
-#ifdef VA_PHASE_CLOCKS
+#if defined(VA_PHASE_CLOCKS) && VA_BWD_PART == VA_PHASE_CLOCKS - 1
 extern "C" int varlen_attn_debug_phase(unsigned long long* out, int reset) {
     if (reset) { unsigned long long z[16] = {}; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z)); }
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase), 16 * sizeof(unsigned long long));

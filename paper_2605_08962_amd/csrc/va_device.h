@@ -327,6 +327,14 @@ __device__ __forceinline__ void interleave_mfma_valu() {
     }
 }
 
+// Moves a loop-invariant MFMA operand into the accumulation half of the register file.  A kernel that
+// runs one wave per SIMD has 512 registers, but the vector ALU only reaches the 256 "architectural"
+// ones; when those run short the compiler parks MFMA RESULTS in the other half and pays one copy
+// instruction per register every time the vector ALU needs them (64 per step for S and dP).  The
+// matrix instructions read their A/B operands from either half, so operands that only they touch
+// are the right thing to keep there.
+__device__ __forceinline__ void park_in_acc_registers(bf16x8& x) { asm volatile("" : "+a"(x)); }
+
 // Forces x to be computed by this point of the program: without it the compiler sinks a value's
 // whole computation into the later block that first uses it, i.e. out of the pipeline slot that was
 // meant to overlap it with matrix work.

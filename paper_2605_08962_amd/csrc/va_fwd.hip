@@ -221,8 +221,8 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     int item, hp;
     xcd_item_head(bid, max_items, Hq, Hkv, item, hp);
     if (item >= hdr[0]) return;
-    ClockProbe clk;
-    clk.begin(clock_probe);
+    ClockProbe wg_clock;
+    wg_clock.begin(clock_probe);
     // Head slots count the kv heads first, so that (with Hkv a multiple of the 8 XCDs) every XCD's L2
     // only ever sees its own kv heads.
     const int kvh = hp % Hkv;
@@ -390,7 +390,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
                                                           oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
                 }
             if (hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = row_lse;
-            clk.end(clock_probe);
+            wg_clock.end(clock_probe);
             return;
         }
         __bf16* op = O + ((size_t)(sb + qrow) * Hq + h) * D;
@@ -408,7 +408,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
             }
         if (hh == 0) LSE[(size_t)h * T + sb + qrow] = row_lse;
     }
-    clk.end(clock_probe);
+    wg_clock.end(clock_probe);
 }
 
 template <int D>
