@@ -706,7 +706,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     const unsigned char* kbase = (const unsigned char*)(K + ((size_t)sb * Hkv + kvh) * D);
     const unsigned char* vbase = (const unsigned char*)(V + ((size_t)sb * Hkv + kvh) * D);
     const uint32_t row_bytes = (uint32_t)Hkv * D * 2;
-    TileDma<D, 64> dma;
+    TileDma<D, 64, D == 80> dma;
     dma.init(row_bytes, L, w, l);
     const uint32_t lds0 = lds_address(lds);
     // Staging, as in the dK/dV kernel: pointers advanced by additions, loads issued unconditionally

@@ -76,12 +76,12 @@ struct LdsTile {
     static constexpr int SLOTS = ROWB / 16;
     static constexpr int CHUNKS = D / 8;              // slots that hold data
     static constexpr int BLOCK_POS = 16 * SLOTS;      // 16-byte positions in a block of 16 rows
-    __host__ __device__ __forceinline__ static int swz(int r) {
+    __host__ __device__ __forceinline__ static constexpr int swz(int r) {
         if (ROWB == 256) return ((r & 3) << 2) | ((r >> 2) & 3);
         const int x = (r >> 1) & 7;
         return ((x & 1) << 2) | (x >> 1);
     }
-    __host__ __device__ __forceinline__ static int off(int r, int c) { return r * ROWB + ((c ^ swz(r)) << 4); }
+    __host__ __device__ __forceinline__ static constexpr int off(int r, int c) { return r * ROWB + ((c ^ swz(r)) << 4); }
     // Byte offset this lane passes to lds_read_tr for the 4 x 16 block at rows row0.., columns
     // 32*db + (0 or 16).. of the tile; row0 must be a multiple of 8 (see tr_lane_offset).
     __host__ __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
@@ -91,7 +91,7 @@ struct LdsTile {
     }
     // Which (row of the block, logical chunk) lives at 16-byte position p of a 16-row block; false
     // for a position that holds no data.  The inverse of off(), used to aim the direct-to-LDS loads.
-    __host__ __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+    __host__ __device__ __forceinline__ static constexpr bool locate(int p, int& r, int& c) {
         r = p / SLOTS;
         c = (p % SLOTS) ^ swz(r);
         return CHUNKS == SLOTS || c < CHUNKS;
@@ -112,12 +112,12 @@ struct LdsTile<80> {
     static constexpr int ROWB = 160;  // nominal: a block of 16 rows is 16 * ROWB bytes
     static constexpr int CHUNKS = 10;
     static constexpr int BLOCK_POS = 160;
-    __host__ __device__ __forceinline__ static int pos(int r, int c) {  // r in [0, 16)
+    __host__ __device__ __forceinline__ static constexpr int pos(int r, int c) {  // r in [0, 16)
         const int a = r >> 2, b = r & 3;
         const int seg = c < 8 ? 2 * a + (c >> 2) : c;
         return 16 * seg + 4 * b + ((c + a) & 3);
     }
-    __host__ __device__ __forceinline__ static int off(int r, int c) { return (r >> 4) * (16 * ROWB) + 16 * pos(r & 15, c); }
+    __host__ __device__ __forceinline__ static constexpr int off(int r, int c) { return (r >> 4) * (16 * ROWB) + 16 * pos(r & 15, c); }
     // Columns 80..95 of the third 32-column block do not exist: the lanes that would address them
     // re-read chunks 8 and 9 (same addresses as their partner lanes; the results are never used).
     __host__ __device__ __forceinline__ static int tr_off(int lane, int row0, int db) {
@@ -126,9 +126,9 @@ struct LdsTile<80> {
         if (c >= CHUNKS) c -= 2;
         return off(r, c) + 8 * (lane & 1);
     }
-    __host__ __device__ __forceinline__ static bool locate(int p, int& r, int& c) {
+    __host__ __device__ __forceinline__ static constexpr bool locate(int p, int& r, int& c) {
         const int seg = p >> 4, b = (p >> 2) & 3, e = p & 3;
-        int a;
+        int a = 0;
         if (seg < 8) { a = seg >> 1; c = 4 * (seg & 1) + ((e - a) & 3); }
         else { c = seg; a = (e - c) & 3; }
         r = 4 * a + b;
@@ -154,6 +154,19 @@ __device__ __forceinline__ uint64_t uniform_u64(const void* p) {
 __device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                  : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory");
+}
+// The same load for the lanes named in `lanes` only (a wave-uniform bit mask).  The execution mask is
+// narrowed inside the assembly statement and put back behind the load, so that the compiler sees no
+// branch: an `if (lane is active)` around the load costs a saved-exec branch per load and, worse, cuts
+// the loop body into basic blocks across which nothing is scheduled.  Must be reached by all 64 lanes.
+__device__ __forceinline__ void dma16_lanes(const void* base, uint32_t byte_off, uint32_t lds_addr, uint64_t lanes) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %4\n\ts_mov_b32 m0, %1\n\t"
+                 "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved)
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)),
+                   "s"(lanes)
+                 : "memory");
 }
 // Same with 4 bytes per lane: lane i's dword lands at lds_addr + 4 * i.
 __device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, uint32_t lds_addr) {
@@ -231,14 +244,40 @@ __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readf
 // the tile's first row; they are computed once per kernel, so that issuing a tile costs no vector
 // ALU work.  `last` holds the offsets for the sample's ragged last tile, where rows past the sample
 // end re-read its last row (finite data that the caller masks).
-template <int D, int ROWS>
+// MASK_BY_BRANCH: partly active loads sit behind an `if (lane active)` instead of narrowing the execution
+// mask in assembly.  The branch cuts the caller's loop body into blocks; one kernel (dQ at head_dim 80,
+// at its register limit) is faster that way because the compiler then hoists less across the loads.
+template <int D, int ROWS, bool MASK_BY_BRANCH = false>
 struct TileDma {
     using T = LdsTile<D>;
     static_assert(ROWS == 64, "one block of 16 rows per wave");
     static constexpr int NI = (T::BLOCK_POS + 63) / 64;  // load instructions per wave per tile
     static constexpr int WAVE_BYTES = 16 * T::ROWB;      // LDS bytes of one wave's 16-row block
     uint32_t full[NI], last[NI];
-    bool active[NI];
+    // lanes of load instruction i that hold data (a compile-time constant of the layout)
+    __device__ __forceinline__ static constexpr uint64_t lane_mask(int i) {
+        uint64_t m = 0;
+        for (int lane = 0; lane < 64; ++lane) {
+            const int p = 64 * i + lane;
+            int r = 0, c = 0;
+            if (p < T::BLOCK_POS && T::locate(p, r, c)) m |= 1ull << lane;
+        }
+        return m;
+    }
+    struct LaneMasks { uint64_t m[NI]; };
+    __device__ __forceinline__ static constexpr LaneMasks lane_masks() {
+        LaneMasks k{};
+        for (int i = 0; i < NI; ++i) k.m[i] = lane_mask(i);
+        return k;
+    }
+    // load instruction i (known after unrolling) of a tile
+    __device__ __forceinline__ static void load(int i, const unsigned char* src, uint32_t off, uint32_t lds_addr) {
+        constexpr LaneMasks k = lane_masks();
+        const uint64_t m = k.m[i];
+        if (m == ~0ull) dma16(src, off, lds_addr);
+        else if (!MASK_BY_BRANCH) dma16_lanes(src, off, lds_addr, m);
+        else if ((m >> (threadIdx.x & 63)) & 1) dma16(src, off, lds_addr);
+    }
     // row_bytes: bytes between consecutive rows of the tensor; L: rows in the sample
     __device__ __forceinline__ void init(uint32_t row_bytes, int L, int wave, int lane) {
         const int last_r0 = (L - 1) / ROWS * ROWS;
@@ -246,7 +285,7 @@ struct TileDma {
         for (int i = 0; i < NI; ++i) {
             const int p = 64 * i + lane;  // position inside this wave's block
             int r = 0, c = 0;
-            active[i] = T::locate(p < T::BLOCK_POS ? p : 0, r, c) && p < T::BLOCK_POS;
+            T::locate(p < T::BLOCK_POS ? p : 0, r, c);  // (a lane without data gets some valid offset; it never loads)
             const int row = 16 * wave + r;
             full[i] = (uint32_t)row * row_bytes + c * 16;
             last[i] = (uint32_t)min(row, L - 1 - last_r0) * row_bytes + c * 16;
@@ -265,7 +304,7 @@ struct TileDma {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const uint32_t off = ragged ? last[i] : full[i];
-            if (active[i]) dma16(src, off, dest(tile, wave, i));
+            load(i, src, off, dest(tile, wave, i));
         }
     }
     // All loads of a tile whose first row's bytes at this head start at src.
@@ -273,13 +312,13 @@ struct TileDma {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const uint32_t off = ragged ? last[i] : full[i];
-            if (active[i]) dma16(src, off, dest(tile, wave, i));
+            load(i, src, off, dest(tile, wave, i));
         }
     }
     // Load instruction i of a tile, i known after unrolling (same as issue_one<i>).
     __device__ __forceinline__ void issue_one_rt(int i, const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
         const uint32_t off = ragged ? last[i] : full[i];
-        if (active[i]) dma16(src, off, dest(tile, wave, i));
+        load(i, src, off, dest(tile, wave, i));
     }
     // One of the NI load instructions of a tile: src = first byte of the tile's first row at this
     // head.  Lets a caller spread a tile's loads over its compute phases: a wave that issues them
@@ -289,7 +328,7 @@ struct TileDma {
     __device__ __forceinline__ void issue_one(const unsigned char* src, bool ragged, uint32_t tile, int wave) const {
         static_assert(I >= 0 && I < NI, "no such load");
         const uint32_t off = ragged ? last[I] : full[I];
-        if (active[I]) dma16(src, off, dest(tile, wave, I));
+        load(I, src, off, dest(tile, wave, I));
     }
 };
 
