@@ -220,6 +220,9 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
     int item, hp;
     xcd_item_head(bid, max_items, Hq, Hkv, item, hp);
+    // (integer division runs on the vector ALU; make the results scalar again, so that what is derived
+    // from them stays in scalar registers)
+    item = __builtin_amdgcn_readfirstlane(item); hp = __builtin_amdgcn_readfirstlane(hp);
     if (item >= hdr[0]) return;
     ClockProbe wg_clock;
     wg_clock.begin(clock_probe);
