@@ -29,12 +29,12 @@ PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 # Read off profiles/bench_vit_d64_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
 # the factors being what the same counters read for a 1 GiB device copy in the same run.
 MEASURED_TRAFFIC_BYTES = {
-    ("long_short_mix_d80", "dkdv"): int((2.0 * 9.295e+06 + 7.499e+05) * 1024),
-    ("long_short_mix_d80", "dq"): int((2.0 * 1.038e+07 + 3.925e+05) * 1024),
-    ("long_short_mix_d80", "fwd"): int((2.0 * 9.134e+06 + 3.834e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 1.129e+06 + 7.16e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.425e+06 + 3.806e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 8.736e+05 + 3.695e+05) * 1024),
+    ("long_short_mix_d80", "dkdv"): int((2.0 * 5.141e+06 + 8.149e+05) * 1024),
+    ("long_short_mix_d80", "dq"): int((2.0 * 5.536e+06 + 3.923e+05) * 1024),
+    ("long_short_mix_d80", "fwd"): int((2.0 * 4.849e+06 + 3.832e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 9.564e+05 + 7.156e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.107e+06 + 3.806e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 6.3e+05 + 3.694e+05) * 1024),
 }
 
 
