@@ -90,11 +90,11 @@ int check_device() {
 
 // How many workgroups share the keys of one query tile in the forward.  Splitting only pays when the
 // launch cannot fill the chip: fewer workgroups than the 256 CUs can hold at once (3 per CU at
-// head_dim <= 64 and at 80 without the causal mask, else 2), and samples long enough that every chunk still gets two key tiles.
+// head_dim <= 80, else 2), and samples long enough that every chunk still gets two key tiles.
 int fwd_kv_splits(const varlen_attn_params* p) {
     if (p->kv_splits >= 1) return p->kv_splits;
     const int64_t wgs = ((int64_t)p->total_tokens / va::FWD_TILE_Q + p->num_seqs) * p->num_q_heads;
-    const int64_t slots = 256 * ((p->head_dim <= 64 || (p->head_dim == 80 && !p->causal)) ? 3 : 2);
+    const int64_t slots = 256 * (p->head_dim <= 80 ? 3 : 2);
     const int64_t tiles_per_sample = (int64_t)p->total_tokens / p->num_seqs / va::FWD_TILE_KV;
     int64_t s = std::min<int64_t>(std::min<int64_t>(slots / std::max<int64_t>(wgs, 1), tiles_per_sample / 2), VA_MAX_KV_SPLITS);
     return (int)std::max<int64_t>(s, 1);

@@ -32,14 +32,16 @@ struct FwdCfg {
 constexpr float kRescaleLog2 = 8.0f;
 
 // One 64-key tile for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// BOUNDARY tiles apply the sample-end / causal mask and carry P as bf16 hi + lo: they are where
-// rows with only a handful of keys live (short samples, the first rows under the causal mask),
-// whose outputs are O(1), so a single bf16 rounding of P would eat most of the 1e-2 tolerance.
+// BOUNDARY tiles apply the sample-end / causal mask.  LO tiles also carry P as bf16 hi + lo: a
+// sample's first key tile, when it is a boundary tile, is where rows with only a handful of keys live
+// (samples shorter than a tile, the first rows under the causal mask); their outputs are O(1), so a
+// single bf16 rounding of P would eat most of the 1e-2 tolerance.  A row that reaches any other
+// boundary tile sees at least 64 keys, and the rounding errors of its P average out.
 // `issue` is called with slot numbers 0..3 spread over the step (FIRST_SLOT..3 only, for a caller that
 // has already run the earlier ones): the caller hangs the tile loads of the iterations ahead on
 // them, so that they trickle into the memory pipeline between the MFMAs instead of queueing up
 // behind every other wave's right after the barrier.
-template <int D, bool CAUSAL, bool BOUNDARY, int FIRST_SLOT = 0, typename Issue>
+template <int D, bool CAUSAL, bool BOUNDARY, int FIRST_SLOT = 0, bool LO = false, typename Issue>
 __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigned char* vb,
                                           const int (&kaddr)[FwdCfg<D>::KS],
                                           const int (&vaddr)[FwdCfg<D>::DB][2],
@@ -121,7 +123,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
                               s[b][8 * st + 4], s[b][8 * st + 5], s[b][8 * st + 6], s[b][8 * st + 7]);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                plo[b][st][e] = BOUNDARY ? (__bf16)(s[b][8 * st + e] - (float)pb[b][st][e]) : (__bf16)0.f;
+                plo[b][st][e] = LO ? (__bf16)(s[b][8 * st + e] - (float)pb[b][st][e]) : (__bf16)0.f;
         }
     issue(2);
 #pragma unroll
@@ -133,7 +135,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
                 const unsigned char* p0 = vb + (32 * b + 16 * st) * ROWB;
                 bf16x8 a = cat4(lds_read_tr(p0 + vaddr[db][0]), lds_read_tr(p0 + vaddr[db][1]));
                 oacc[db] = mfma32(a, pb[b][st], oacc[db]);
-                if (BOUNDARY) oacc[db] = mfma32(a, plo[b][st], oacc[db]);
+                if (LO) oacc[db] = mfma32(a, plo[b][st], oacc[db]);
             }
         if (db == 0) issue(3);
     }
@@ -198,10 +200,9 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
     return true;
 }
 
-// Workgroups per CU the kernel is compiled for (registers) and its LDS allows: head_dim 80 fits three
-// only without the causal mask, whose boundary path needs more registers.
+// Workgroups per CU the kernel is compiled for (registers) and its LDS allows.
 template <int D, bool CAUSAL>
-constexpr int kFwdWgsPerCu = (D <= 64 || (D == 80 && !CAUSAL)) ? 3 : 2;
+constexpr int kFwdWgsPerCu = D <= 80 ? 3 : 2;
 
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
@@ -244,7 +245,6 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // tiles [0, n_plain) need no mask in any wave: whole tiles below the sample end and, under the
     // causal mask, entirely at or below the tile's first query row
     const int n_plain = CAUSAL ? min(L, q0 + 1) / C::BKV : L / C::BKV;
-    const int wq_lo = q0 + 32 * w, wq_hi = wq_lo + 31;  // this wave's query rows
     const int jb = S > 1 ? ntiles * ch / S : 0, je = S > 1 ? ntiles * (ch + 1) / S : ntiles;  // this chunk's tiles
     if (jb >= je) {  // fewer tiles than chunks: an empty part (its O is never read)
         if (qvalid && hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = -INFINITY;
@@ -339,6 +339,12 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
         kslot = kslot == 2 ? 0 : kslot + 1;                                                    \
         vslot ^= 1;
 
+    if (n_plain == 0 && j == 0) {  // a sample's first key tile with a mask: rows with very few keys (hi + lo P)
+        VA_FWD_ITER_BEGIN()
+        tile_step<D, CAUSAL, true, 0, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+        VA_FWD_ITER_END()
+        ++j;
+    }
     if (j < min(n_plain, je)) {  // the first mask-free tile sets the reference maximum
         VA_FWD_ITER_BEGIN()
         tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
@@ -359,14 +365,12 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     }
     for (; j < je; ++j) {  // the sample's ragged last tile and the causal diagonal
         VA_FWD_ITER_BEGIN()
-        // causal: a wave whose rows all lie above this key tile has nothing to add (but still loads).
-        // (every wave takes the masked variant here, also one whose rows see the whole tile: a second
-        // variant in this loop makes the compiler keep two sets of accumulator registers and spill)
-        if (!CAUSAL || kv0 <= wq_hi) {
-            tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
-        } else {
-            issue(0); issue(1); issue(2); issue(3);
-        }
+        // Every wave takes the masked variant here, also one whose rows see the whole tile or none of it
+        // (causal: rows above the key tile; such a wave adds exact zeros).  A second variant in this loop
+        // makes the compiler keep two sets of accumulator registers, and letting the idle wave skip the
+        // step costs 30 to 60 registers for the branch around it (one workgroup per CU less at head_dim
+        // 64): it has to wait at the barrier for the other waves anyway.
+        tile_step<D, CAUSAL, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
         VA_FWD_ITER_END()
     }
     wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
