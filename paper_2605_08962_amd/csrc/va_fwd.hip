@@ -353,14 +353,9 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     }
     for (; j < min(n_plain, je); ++j) {  // no masks, every wave active, maximum taken on trust
         VA_FWD_ITER_BEGIN()
-        // (measured: worth 2 % at head_dim 64 and 80, where the vector ALU is the busier pipe; at 128
-        // the matrix pipe is, and the second code path only costs registers)
-        if constexpr (D > 96) {
-            tile_step<D, CAUSAL, false>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
-        } else {
-            if (!tile_step_trusting<D>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, issue))
-                tile_step<D, CAUSAL, false, 2>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
-        }
+        // (measured: worth 2 % at head_dim 64 and 80, where the vector ALU is the busier pipe, 1.5 % at 128)
+        if (!tile_step_trusting<D>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, issue))
+            tile_step<D, CAUSAL, false, 2>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
         VA_FWD_ITER_END()
     }
     for (; j < je; ++j) {  // the sample's ragged last tile and the causal diagonal
