@@ -29,12 +29,12 @@ PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 # Read off profiles/bench_vit_d64_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
 # the factors being what the same counters read for a 1 GiB device copy in the same run.
 MEASURED_TRAFFIC_BYTES = {
-    ("long_short_mix_d80", "dkdv"): int((2.0 * 5.141e+06 + 8.149e+05) * 1024),
-    ("long_short_mix_d80", "dq"): int((2.0 * 5.536e+06 + 3.923e+05) * 1024),
-    ("long_short_mix_d80", "fwd"): int((2.0 * 4.849e+06 + 3.832e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 9.564e+05 + 7.156e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.107e+06 + 3.806e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 6.3e+05 + 3.694e+05) * 1024),
+    ("long_short_mix_d80", "dkdv"): int((2.0 * 5.14e+06 + 8.147e+05) * 1024),
+    ("long_short_mix_d80", "dq"): int((2.0 * 5.531e+06 + 3.923e+05) * 1024),
+    ("long_short_mix_d80", "fwd"): int((2.0 * 4.851e+06 + 3.833e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 9.467e+05 + 7.157e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.101e+06 + 3.806e+05) * 1024),
+    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 6.169e+05 + 3.694e+05) * 1024),
 }
 
 
