@@ -281,6 +281,47 @@ def vendor_reference(args, torch, binding):
         torch.cuda.empty_cache()
 
 
+def short_regime(args, torch, binding):
+    """The short-sequence regime: equal-length samples of 64..2048 tokens (about 84k tokens per batch, 16
+    heads), forward and backward, as HBM GB/s at the minimum bytes (every input read once, every output
+    written once) next to useful TFLOP/s.  Median of HIP events over args.steps calls."""
+    print("| D | L | samples | pass | us | GB/s at min bytes | % of 8 TB/s | useful TFLOP/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    H = 16
+    for D in (64, 80, 128):
+        for L in (64, 128, 256, 512, 1024, 2048):
+            B = 84000 // L
+            T = B * L
+            g = torch.Generator(device="cuda"); g.manual_seed(D + L)
+            q, k, v, do = (torch.randn((T, H, D), device="cuda", dtype=torch.bfloat16, generator=g) for _ in range(4))
+            cu = torch.arange(0, T + 1, L, dtype=torch.int32, device="cuda")
+            scale = D ** -0.5
+            p = binding.make_params(T, B, H, H, D, False, scale)
+            ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+            ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+            o = torch.empty_like(q)
+            lse = torch.empty((H, T), dtype=torch.float32, device="cuda")
+            dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+            fns = (("fwd", lambda: binding.varlen_attn_fwd(q, k, v, cu, False, scale, out=o, lse=lse, workspace=ws_f),
+                    2 * D * T * 4 * H + 4 * T * H, 1.0),
+                   ("bwd", lambda: binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, False, scale, dq=dq, dk=dk, dv=dv,
+                                                           workspace=ws_b),
+                    2 * D * T * 8 * H + 4 * T * H, 2.5))
+            for name, fn, nbytes, mult in fns:
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                ts = []
+                for _ in range(args.steps):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+                    ts.append(e0.elapsed_time(e1))
+                ms = float(np.median(ts))
+                flops = mult * 4.0 * D * H * B * L * L
+                print(f"| {D} | {L} | {B} | {name} | {ms * 1e3:.0f} | {nbytes / ms / 1e6:.0f} | "
+                      f"{100 * nbytes / ms / 1e6 / 8000:.0f} | {flops / ms / 1e9:.0f} |", flush=True)
+
+
 def small_launch(args, torch, binding, W):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(77)
@@ -357,6 +398,9 @@ def main():
                     help="instead of the one JSON line: forward on launches too small to fill the GPU with and "
                          "without splitting each query tile's keys over several workgroups, and the merge "
                          "primitive's HBM rate; prints markdown tables")
+    ap.add_argument("--short-regime", action="store_true",
+                    help="equal-length samples of 64..2048 tokens: HBM GB/s at the minimum bytes and useful "
+                         "TFLOP/s, forward and backward; prints a markdown table")
     ap.add_argument("--vendor-reference", action="store_true",
                     help="context: time this library and PyTorch's own fused attention on the same box on "
                          "equal-length samples; prints a markdown table")
@@ -391,6 +435,9 @@ def main():
         return
     if args.vendor_reference:
         vendor_reference(args, torch, binding)
+        return
+    if args.short_regime:
+        short_regime(args, torch, binding)
         return
 
     with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5

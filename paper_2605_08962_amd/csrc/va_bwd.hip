@@ -297,7 +297,7 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     int item, c;  // work item and kv head (see xcd_item_head)
-    xcd_item_head(blockIdx.x, max_items, Hkv, Hkv, item, c);
+    xcd_item_head(blockIdx.x, max_items, Hkv, Hkv, hdr[1], item, c);
     // (integer division runs on the vector ALU: without this, everything derived from the two, the
     // staging pointers included, would be kept in vector registers and advanced there)
     item = __builtin_amdgcn_readfirstlane(item); c = __builtin_amdgcn_readfirstlane(c);
@@ -688,7 +688,7 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     int item, hp;
-    xcd_item_head(blockIdx.x, max_items, Hq, Hkv, item, hp);
+    xcd_item_head(blockIdx.x, max_items, Hq, Hkv, hdr[1], item, hp);
     item = __builtin_amdgcn_readfirstlane(item); hp = __builtin_amdgcn_readfirstlane(hp);  // see dkdv_kernel
     if (item >= hdr[0]) return;
     ClockProbe wg_clock;

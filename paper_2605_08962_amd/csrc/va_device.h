@@ -209,22 +209,30 @@ struct ClockProbe {
 // for kv head hp % kv_heads and member hp / kv_heads of its group of query heads.  Workgroup ids are
 // dealt round-robin to the 8 XCDs, each with an L2 of its own.  With kv_heads a multiple of 8, XCD x
 // gets the kv heads x, x + 8, ... and all their query heads.  It walks the (cost-sorted) work list in
-// chunks of kXcdChunk items and finishes a chunk for one kv head (all query heads of the group side by
-// side: they read the same K/V) before it takes the chunk for its next kv head.  The workgroups running
-// together on an XCD thus stream the K/V (or Q/dO) of ONE kv head where a plain item-major order
-// interleaves all of the XCD's heads: the same bytes serve more workgroups and stay in L2 for longer.
+// chunks of `chunk` items and finishes a chunk for one kv head (all query heads of the group side by
+// side: they read the same K/V) before it takes the chunk for its next kv head.
+//   chunk = kXcdChunk (long samples): the workgroups running together on an XCD stream the K/V (or
+//     Q/dO) of ONE kv head where an item-major order interleaves all of the XCD's heads; the same bytes
+//     serve more workgroups and stay in L2 for longer (HBM-side traffic of a 65536-token sample halved).
+//   chunk = 1 (short samples only; item-major): the workgroups of all heads of an item run together and
+//     read whole token rows of Q/K/V at once.  Nothing is re-read in this regime, and visiting every
+//     DRAM row once instead of once per head of the XCD is worth 10 % at 128-token samples.
+// The scheduler kernel picks the chunk from the longest sample and leaves it in its header.
 constexpr int kXcdChunk = 128;
-__host__ __device__ __forceinline__ void xcd_item_head(unsigned bid, int n_items, int heads, int kv_heads, int& item, int& hp) {
+constexpr int kXcdChunkMinLen = 1024;  // longest sample from which the chunked order is used
+__host__ __device__ __forceinline__ void xcd_item_head(unsigned bid, int n_items, int heads, int kv_heads, int chunk,
+                                                       int& item, int& hp) {
     if (kv_heads % 8 != 0) { item = (int)(bid / (unsigned)heads); hp = (int)(bid % (unsigned)heads); return; }
+    const unsigned C = (unsigned)chunk;
     const unsigned g = (unsigned)(heads / kv_heads), kx = (unsigned)kv_heads / 8;
-    const unsigned x = bid % 8, k = bid / 8;                          // k-th workgroup of XCD x
-    const unsigned full = (unsigned)n_items / kXcdChunk * kXcdChunk;  // items in whole chunks
-    const unsigned per_chunk = kXcdChunk * g;                         // workgroups of one (chunk, kv head)
+    const unsigned x = bid % 8, k = bid / 8;        // k-th workgroup of XCD x
+    const unsigned full = (unsigned)n_items / C * C;  // items in whole chunks
+    const unsigned per_chunk = C * g;                 // workgroups of one (chunk, kv head)
     unsigned kvslot, i, gq;
     if (k < full * g * kx) {
         const unsigned c = k / (per_chunk * kx), rem = k % (per_chunk * kx);
         kvslot = rem / per_chunk;
-        i = c * kXcdChunk + (rem % per_chunk) / g;
+        i = c * C + (rem % per_chunk) / g;
         gq = rem % g;
     } else {
         const unsigned kk = k - full * g * kx, r = (unsigned)n_items - full;

@@ -220,7 +220,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const int ch = S > 1 ? (int)(blockIdx.x % S) : 0;
     const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
     int item, hp;
-    xcd_item_head(bid, max_items, Hq, Hkv, item, hp);
+    xcd_item_head(bid, max_items, Hq, Hkv, hdr[1], item, hp);
     // (integer division runs on the vector ALU; make the results scalar again, so that what is derived
     // from them stays in scalar registers)
     item = __builtin_amdgcn_readfirstlane(item); hp = __builtin_amdgcn_readfirstlane(hp);

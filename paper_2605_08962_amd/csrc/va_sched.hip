@@ -8,6 +8,7 @@
 // over), entirely on the device.  The compute kernels launch one workgroup per (list entry,
 // head) in list order, so the hardware dispatcher hands out the heaviest tiles first and the
 // light ones fill the tail (longest-processing-time-first list scheduling).
+#include "va_device.h"
 #include "va_internal.h"
 
 namespace va {
@@ -58,14 +59,21 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
              int32_t* __restrict__ tile_off, WorkItem* __restrict__ items) {
     __shared__ int scan_buf[SCHED_THREADS];
     __shared__ int bins[SCHED_BINS];
+    __shared__ int longest;
     const int t = threadIdx.x;
+    if (t == 0) longest = 0;
+    __syncthreads();
 
     // 1. tile_off[s] = number of tiles of samples 0..s-1
     int carry = 0;
     for (int base = 0; base < B; base += SCHED_THREADS) {
         int s = base + t;
         int n = 0;
-        if (s < B) n = (cu[s + 1] - cu[s] + R - 1) / R;
+        if (s < B) {
+            const int len = cu[s + 1] - cu[s];
+            n = (len + R - 1) / R;
+            if (len >= kXcdChunkMinLen) longest = len;  // (any such length will do: only the threshold matters)
+        }
         int total;
         int ex = block_exclusive_scan(n, scan_buf, &total);
         if (s < B) tile_off[s] = carry + ex;
@@ -75,6 +83,7 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
     if (t == 0) {
         tile_off[B] = n_items;
         hdr[0] = n_items;
+        hdr[1] = longest >= kXcdChunkMinLen ? kXcdChunk : 1;  // work order of the compute kernels (xcd_item_head)
     }
     for (int i = t; i < SCHED_BINS; i += SCHED_THREADS) bins[i] = 0;
     __syncthreads();  // also makes tile_off (global, written by this block) visible to the block

@@ -58,14 +58,16 @@ static int check_work_order() {
     int bad = 0;
     for (auto& sh : shapes) {
         const int n = sh[0], heads = sh[1], kv = sh[2];
-        std::set<std::pair<int, int>> seen;
-        for (unsigned bid = 0; bid < (unsigned)(n * heads); ++bid) {
-            int item, hp;
-            va::xcd_item_head(bid, n, heads, kv, item, hp);
-            if (item < 0 || item >= n || hp < 0 || hp >= heads || !seen.insert({item, hp}).second) ++bad;
-            if (kv % 8 == 0 && (hp % kv) % 8 != (int)(bid % 8)) ++bad;  // the kv head stays on its XCD
+        for (int chunk : {1, va::kXcdChunk}) {
+            std::set<std::pair<int, int>> seen;
+            for (unsigned bid = 0; bid < (unsigned)(n * heads); ++bid) {
+                int item, hp;
+                va::xcd_item_head(bid, n, heads, kv, chunk, item, hp);
+                if (item < 0 || item >= n || hp < 0 || hp >= heads || !seen.insert({item, hp}).second) ++bad;
+                if (kv % 8 == 0 && (hp % kv) % 8 != (int)(bid % 8)) ++bad;  // the kv head stays on its XCD
+            }
+            if (bad) std::printf("work order n=%d heads=%d kv=%d chunk=%d: %d errors\n", n, heads, kv, chunk, bad);
         }
-        if (bad) std::printf("work order n=%d heads=%d kv=%d: %d errors\n", n, heads, kv, bad);
     }
     return bad;
 }
