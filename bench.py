@@ -2,7 +2,7 @@
 """Benchmark of the varlen packed attention hot path on one MI355X.
 
 A step is one pass of the whole path on one synthetic batch: forward (scheduler + attention kernel)
-followed by backward (two schedulers, Delta, dK/dV, dQ).  The default workload is the ViT encoder
+followed by backward (two schedulers, dQ with the row statistics, dK/dV).  The default workload is the ViT encoder
 layer with dynamic resolution: 64 images of 256..9216 tokens packed non-causally, 16 heads, head_dim
 64, bf16, forward + backward.  Inputs are resident in HBM before the timed region starts.
 

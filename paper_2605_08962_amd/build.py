@@ -39,15 +39,18 @@ def _compile(item):
 
 
 UBENCH = os.path.join(HERE, "ubench_mfma_valu")
+UBENCH_ATOMIC = os.path.join(HERE, "ubench_atomic_rate")
 
 
 def build_ubench():
-    """The stand-alone MFMA / vector-ALU overlap microbenchmark (csrc/ubench_mfma_valu.hip)."""
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, "ubench_mfma_valu.hip"), "-o", UBENCH]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed on ubench_mfma_valu.hip:\n" + r.stderr)
+    """The stand-alone microbenchmarks: MFMA / vector-ALU overlap (csrc/ubench_mfma_valu.hip) and the fp32
+    atomic-add rate that rules out a one-kernel backward (csrc/ubench_atomic_rate.hip)."""
+    for src, out in (("ubench_mfma_valu.hip", UBENCH), ("ubench_atomic_rate.hip", UBENCH_ATOMIC)):
+        cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               os.path.join(CSRC, src), "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n" + r.stderr)
     return UBENCH
 
 
