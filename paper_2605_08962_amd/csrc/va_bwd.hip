@@ -68,8 +68,8 @@ __device__ __forceinline__ bf16x8 pack_regs_lo(const f32x16& x, int st, bf16x8 h
 // ------------------------------------------------------------------------------------------------
 // dK, dV
 // ------------------------------------------------------------------------------------------------
-// One 64-query step for one wave (32 keys).  MASKED steps apply the causal / sample-end mask and
-// carry P and dS as bf16 hi + lo (see the forward kernel for why).
+// One 64-query step for one wave (32 keys).  MASKED steps apply the causal / sample-end mask and, where
+// `lo` is set (wave-uniform), carry P and dS as bf16 hi + lo (see the forward kernel for why).
 //   qt, dot : LDS tiles of Q and dO (64 rows);  stat: per 16 rows {16 x lse2, 16 x delta}
 //   aaddr   : per-lane offsets of the row-wise 16-byte reads, taddr: of the transposing reads
 template <int D, bool CAUSAL, bool MASKED>
@@ -78,9 +78,12 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
                                           const int (&taddr)[BwdCfg<D>::DB][2],
                                           const bf16x8 (&kf)[BwdCfg<D>::KS], const bf16x8 (&vf)[BwdCfg<D>::KS],
                                           f32x16 (&dkacc)[BwdCfg<D>::DB], f32x16 (&dvacc)[BwdCfg<D>::DB],
-                                          float c2, int q0, int kv, int L, int hh) {
+                                          float c2, int q0, int kv, int L, int hh, bool lo = MASKED) {
     using C = BwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
+    // without the causal mask every masked step carries lo parts, next to the hi parts' MFMAs; under it few
+    // steps do (`lo`), in a pass of their own behind one wave-uniform branch
+    constexpr bool LO_INLINE = MASKED && !CAUSAL;
     // The two 32-query halves of the step are handled one after the other, so that only one half's
     // scores and dP (2 x 16 registers) are live at a time.
 #pragma unroll
@@ -125,16 +128,31 @@ __device__ __forceinline__ void dkdv_step(const unsigned char* qt, const unsigne
             const bf16x8 pb = pack_regs(s, st);
             const bf16x8 dsb = pack_regs(dp, st);
             bf16x8 pl, dsl;
-            if (MASKED) { pl = pack_regs_lo(s, st, pb); dsl = pack_regs_lo(dp, st, dsb); }
+            if (LO_INLINE) { pl = pack_regs_lo(s, st, pb); dsl = pack_regs_lo(dp, st, dsb); }
             const int rowoff = (32 * qb + 16 * st) * ROWB;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
                 bf16x8 ado = cat4(lds_read_tr(dot + rowoff + taddr[db][0]), lds_read_tr(dot + rowoff + taddr[db][1]));
                 dvacc[db] = mfma32(ado, pb, dvacc[db]);
-                if (MASKED) dvacc[db] = mfma32(ado, pl, dvacc[db]);
+                if (LO_INLINE) dvacc[db] = mfma32(ado, pl, dvacc[db]);
                 bf16x8 aq = cat4(lds_read_tr(qt + rowoff + taddr[db][0]), lds_read_tr(qt + rowoff + taddr[db][1]));
                 dkacc[db] = mfma32(aq, dsb, dkacc[db]);
-                if (MASKED) dkacc[db] = mfma32(aq, dsl, dkacc[db]);
+                if (LO_INLINE) dkacc[db] = mfma32(aq, dsl, dkacc[db]);
+            }
+        }
+        if (MASKED && CAUSAL && lo) {
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const bf16x8 pl = pack_regs_lo(s, st, pack_regs(s, st));
+                const bf16x8 dsl = pack_regs_lo(dp, st, pack_regs(dp, st));
+                const int rowoff = (32 * qb + 16 * st) * ROWB;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db) {
+                    bf16x8 ado = cat4(lds_read_tr(dot + rowoff + taddr[db][0]), lds_read_tr(dot + rowoff + taddr[db][1]));
+                    dvacc[db] = mfma32(ado, pl, dvacc[db]);
+                    bf16x8 aq = cat4(lds_read_tr(qt + rowoff + taddr[db][0]), lds_read_tr(qt + rowoff + taddr[db][1]));
+                    dkacc[db] = mfma32(aq, dsl, dkacc[db]);
+                }
             }
         }
     }
@@ -416,6 +434,8 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
     const float c2 = scale * kLog2e;
     const int wk_lo = kv0 + 32 * w;
+    // causal: only rows near a sample's start hold few terms, and those meet key tile 0 only
+    const bool lo_steps = !CAUSAL || kv0 == 0;
 
     // Stage protocol.  Step i lives in stage i % NST.  VA_DKDV_SYNC() ends the part of step idx that
     // reads stage idx - 1: it waits until step idx + 1 has landed (with four stages step idx + 2,
@@ -442,72 +462,76 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
            step here takes the masked variant (a superset of the plain one) to keep code small */ \
         if (!CAUSAL || q0 + BWD_STEP_Q - 1 >= wk_lo)                                     \
             dkdv_step<D, CAUSAL, true>(b, b + C::TILE, b + 2 * C::TILE, aaddr, taddr, kf, vf, dkacc, dvacc, \
-                                       c2, q0, kv, L, hh);                               \
+                                       c2, q0, kv, L, hh, lo_steps);                     \
         VA_DKDV_SYNC()                                                                   \
         issue_all();                                                                     \
         VA_DKDV_ADVANCE()                                                                \
     }
 
+    // The mask-free step in phases.  Per half: phase A (S, dP MFMAs), phase B (vector ALU), phase C (dV, dK
+    // MFMAs); each phase also issues the LDS reads of the phase after it.  The step's sync
+    // sits at its start: it only has to retire stage idx - 1, and having stage idx + 1
+    // published early lets the last phase fetch the next step's first operands.
+    DkdvOpsA<D> fa;
+    DkdvOpsC<D> fc;
+    f32x16 s, dpa, dpb;  // dP accumulators of the even / odd half, preloaded with -Delta
+    float lv[16];
+    bf16x8 pb[2], dsb[2];
+    auto phased = [&]() {
+        VA_CLK(0)
+        VA_DKDV_SYNC()
+        const unsigned char* cur = lds + stage_i * STAGE;
+        const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
+        // half 0 (the scalar bookkeeping of this step's loads runs behind its MFMAs)
+        dkdv_load_lse<D, 0>(cur, lv, hh);
+        dkdv_run_S<D>(fa, kf, s);
+        begin_issue();
+        __builtin_amdgcn_sched_barrier(0);
+        VA_DKDV_ISSUE_SLOT(0)
+        VA_DKDV_ISSUE_SLOT(1)
+        VA_CLK(3)
+        dkdv_load_C<D, 0>(cur, taddr, fc);
+        dkdv_run_dP<D>(fa, vf, dpa);
+        dkdv_run_B(s, dpa, lv, c2, pb, dsb);
+        dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+        dkdv_load_A<D, 1>(cur, aaddr, fa, dpb, hh);
+        dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
+        dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
+        __builtin_amdgcn_sched_barrier(0);
+        VA_DKDV_ISSUE_SLOT(2)
+        VA_CLK(4)
+        // half 1
+        dkdv_load_lse<D, 1>(cur, lv, hh);
+        dkdv_run_S<D>(fa, kf, s);
+        __builtin_amdgcn_sched_barrier(0);
+        VA_DKDV_ISSUE_SLOT(3)
+        VA_DKDV_ISSUE_SLOT(4)
+        VA_CLK(5)
+        dkdv_load_C<D, 1>(cur, taddr, fc);
+        dkdv_run_dP<D>(fa, vf, dpb);
+        dkdv_run_B(s, dpb, lv, c2, pb, dsb);
+        dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
+        dkdv_load_A<D, 0>(nxt, aaddr, fa, dpa, hh);  // next step (dropped after the last one)
+        dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
+        dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
+        __builtin_amdgcn_sched_barrier(0);
+        VA_DKDV_ISSUE_SLOT(5)
+        VA_CLK(6)
+#ifdef VA_PHASE_CLOCKS
+        VA_CLK_ACCUM(6)
+        ++nplain;
+#endif
+        VA_DKDV_ADVANCE()
+    };
+
+    // Masked steps (the causal diagonal, the one that holds the sample's end) take the simple form: in
+    // phases, with the mask and the lo parts on top, they were measured no faster even at one wave per SIMD.
     for (int hg = 0; hg < g; ++hg) {
         int st = 0;
         for (; st < n_head; ++st) VA_DKDV_CAREFUL(st)
         if (st < n_tail) {
-            // Mask-free steps.  Per half: phase A (S, dP MFMAs), phase B (vector ALU), phase C (dV, dK
-            // MFMAs); each phase also issues the LDS reads of the phase after it.  The step's sync
-            // sits at its start: it only has to retire stage idx - 1, and having stage idx + 1
-            // published early lets the last phase fetch the next step's first operands.
-            DkdvOpsA<D> fa;
-            DkdvOpsC<D> fc;
-            f32x16 s, dpa, dpb;  // dP accumulators of the even / odd half, preloaded with -Delta
-            float lv[16];
-            bf16x8 pb[2], dsb[2];
             dkdv_load_A<D, 0>(lds + stage_i * STAGE, aaddr, fa, dpa, hh);
-            for (; st < n_tail; ++st) {
-                VA_CLK(0)
-                VA_DKDV_SYNC()
-                const unsigned char* cur = lds + stage_i * STAGE;
-                const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
-                // half 0 (the scalar bookkeeping of this step's loads runs behind its MFMAs)
-                dkdv_load_lse<D, 0>(cur, lv, hh);
-                dkdv_run_S<D>(fa, kf, s);
-                begin_issue();
-                __builtin_amdgcn_sched_barrier(0);
-                VA_DKDV_ISSUE_SLOT(0)
-                VA_DKDV_ISSUE_SLOT(1)
-                VA_CLK(3)
-                dkdv_load_C<D, 0>(cur, taddr, fc);
-                dkdv_run_dP<D>(fa, vf, dpa);
-                dkdv_run_B(s, dpa, lv, c2, pb, dsb);
-                dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
-                dkdv_load_A<D, 1>(cur, aaddr, fa, dpb, hh);
-                dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
-                dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
-                __builtin_amdgcn_sched_barrier(0);
-                VA_DKDV_ISSUE_SLOT(2)
-                VA_CLK(4)
-                // half 1
-                dkdv_load_lse<D, 1>(cur, lv, hh);
-                dkdv_run_S<D>(fa, kf, s);
-                __builtin_amdgcn_sched_barrier(0);
-                VA_DKDV_ISSUE_SLOT(3)
-                VA_DKDV_ISSUE_SLOT(4)
-                VA_CLK(5)
-                dkdv_load_C<D, 1>(cur, taddr, fc);
-                dkdv_run_dP<D>(fa, vf, dpb);
-                dkdv_run_B(s, dpb, lv, c2, pb, dsb);
-                dkdv_run_C<D>(fc, pb, dsb, dkacc, dvacc);
-                dkdv_load_A<D, 0>(nxt, aaddr, fa, dpa, hh);  // next step (dropped after the last one)
-                dkdv_interleave<C::KS, 8 * C::DB / C::KS, 14>();   // dP; dV/dK operand reads; P
-                dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
-                __builtin_amdgcn_sched_barrier(0);
-                VA_DKDV_ISSUE_SLOT(5)
-                VA_CLK(6)
-#ifdef VA_PHASE_CLOCKS
-                VA_CLK_ACCUM(6)
-                ++nplain;
-#endif
-                VA_DKDV_ADVANCE()
-            }
+            for (; st < n_tail; ++st) phased();
         }
         for (; st < nsteps; ++st) VA_DKDV_CAREFUL(st)
     }
@@ -588,7 +612,7 @@ __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned 
                                         const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
                                         const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
                                         f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
-                                        int kv0, int qrow, int L, int hh) {
+                                        int kv0, int qrow, int L, int hh, bool lo = MASKED) {
     using C = BwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
     f32x16 s[2], dp[2];
@@ -616,21 +640,36 @@ __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned 
             }
             dp[b][r] = p * (dp[b][r] + ndelta);
         }
+    constexpr bool LO_INLINE = MASKED && !CAUSAL;  // as in dkdv_step
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             const bf16x8 dsb = pack_regs(dp[b], st);
             bf16x8 dsl;
-            if (MASKED) dsl = pack_regs_lo(dp[b], st, dsb);
+            if (LO_INLINE) dsl = pack_regs_lo(dp[b], st, dsb);
             const int rowoff = (32 * b + 16 * st) * ROWB;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
                 bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
                 dqacc[db] = mfma32(ak, dsb, dqacc[db]);
-                if (MASKED) dqacc[db] = mfma32(ak, dsl, dqacc[db]);
+                if (LO_INLINE) dqacc[db] = mfma32(ak, dsl, dqacc[db]);
             }
         }
+    if (MASKED && CAUSAL && lo) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const bf16x8 dsl = pack_regs_lo(dp[b], st, pack_regs(dp[b], st));
+                const int rowoff = (32 * b + 16 * st) * ROWB;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db) {
+                    bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
+                    dqacc[db] = mfma32(ak, dsl, dqacc[db]);
+                }
+            }
+    }
 }
 
 // ---- the mask-free dQ step in phases (see the dK/dV kernel): S | dP with exp in its shadow | dQ
@@ -791,81 +830,97 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 #pragma unroll
         for (int r = 0; r < 16; ++r) dqacc[db][r] = 0.f;
     const float c2 = scale * kLog2e;
-    const int wq_hi = q0 + 32 * w + 31;
+    // causal: only a sample's first rows hold few terms, and only those need dS as bf16 hi + lo
+    const bool lo_steps = !CAUSAL || q0 == 0;
 
-    // Stage protocol as in the dK/dV kernel: step i lives in stage i % 4; VA_DQ_SYNC() waits until step
-    // j + 1 has landed (step j + 2 may stay in flight) and passes the barrier after which stage j - 1
-    // is free for step j + 3.
+    // Stage protocol as in the dK/dV kernel: step i lives in stage i % 4; the sync at the start of a step
+    // waits until step i + 1 has landed (step i + 2 may stay in flight) and passes the barrier, after
+    // which every wave is done with step i - 1, whose stage this step's loads refill.
     int stage_i = 0;
     int j = 0;
-#define VA_DQ_SYNC()      \
-        wait_vmcnt<PER>();    \
+    f32x16 nd16, zero16;  // -Delta of this lane's row as the starting value of dP; 0 for S
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { nd16[r] = ndelta; zero16[r] = 0.f; }
+    DqOpsA<D> fa;  // K rows for S, then V rows for dP
+    DqOpsA<D> fv;
+    DqOpsT<D> ft;
+    f32x16 s[2], dp[2];
+    dq_load_A<D>(lds + stage_i * STAGE, aaddr, fa);
+    // One key step in phases.  Masked steps (the causal diagonal, the sample's end) zero P outside the
+    // mask; fully masked waves run them all the same, they would only wait at the next barrier.
+    auto step = [&](auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        wait_vmcnt<PER>();
         wg_barrier();
-#define VA_DQ_ADVANCE() stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
-#define VA_DQ_CAREFUL()                                                                           \
-    {                                                                                                 \
-        const int kv0 = j * BWD_STEP_KV;                                                              \
-        const unsigned char* b = lds + stage_i * STAGE;                                               \
-        /* causal: a wave whose rows all lie above this key step has nothing to add; every other step \
-           here takes the masked variant (a superset of the plain one) to keep the code small */      \
-        if (!CAUSAL || kv0 <= wq_hi)                                                                  \
-            dq_step<D, CAUSAL, true>(b, b + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta, kv0, qrow, L, hh); \
-        VA_DQ_SYNC()                                                                                  \
-        issue_all();                                                                                  \
-        VA_DQ_ADVANCE()                                                                               \
-    }
-
-    if (j < n_plain) {
-        f32x16 nd16, zero16;  // -Delta of this lane's row as the starting value of dP; 0 for S
+        const unsigned char* cur = lds + stage_i * STAGE;
+        const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
+        // S^T = K Q^T; meanwhile fetch the V rows and do the scalar bookkeeping of this step's loads
+        dq_load_A<D>(cur + C::TILE, aaddr, fv);
+        dq_run_A<D>(fa, qf, zero16, s);
+        begin_issue();
+        __builtin_amdgcn_sched_barrier(0);
+        dma.issue_tile(iss_k, iss_ragged, iss_lds, w);
+        // dP^T = V dO^T - Delta with P = exp2(c2 S - lse2) in its shadow; meanwhile fetch K^T
+        dq_load_T<D>(cur, taddr, ft);
+        dq_run_A<D>(fv, dof, nd16, dp);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { nd16[r] = ndelta; zero16[r] = 0.f; }
-        DqOpsA<D> fa;  // K rows for S, then V rows for dP
-        DqOpsA<D> fv;
-        DqOpsT<D> ft;
-        f32x16 s[2], dp[2];
-        dq_load_A<D>(lds + stage_i * STAGE, aaddr, fa);
-        for (; j < n_plain; ++j) {
-            VA_DQ_SYNC()
-            const unsigned char* cur = lds + stage_i * STAGE;
-            const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
-            // S^T = K Q^T; meanwhile fetch the V rows and do the scalar bookkeeping of this step's loads
-            dq_load_A<D>(cur + C::TILE, aaddr, fv);
-            dq_run_A<D>(fa, qf, zero16, s);
-            begin_issue();
-            __builtin_amdgcn_sched_barrier(0);
-            dma.issue_tile(iss_k, iss_ragged, iss_lds, w);
-            // dP^T = V dO^T - Delta with P = exp2(c2 S - lse2) in its shadow; meanwhile fetch K^T
-            dq_load_T<D>(cur, taddr, ft);
-            dq_run_A<D>(fv, dof, nd16, dp);
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int r = 0; r < 16; ++r) {
+                float p = fast_exp2(__builtin_fmaf(s[b][r], c2, -lse2));
+                if (MASKED) {
+                    const int kv = j * BWD_STEP_KV + 32 * b + 8 * (r / 4) + 4 * hh + (r % 4);
+                    const bool ok = kv < L && qrow < L && (!CAUSAL || kv <= qrow);
+                    p = ok ? p : 0.f;
+                }
+                s[b][r] = p;
+            }
+        dkdv_interleave<2 * C::KS, 4 * C::DB / C::KS, 8>();
+        __builtin_amdgcn_sched_barrier(0);
+        dma.issue_tile(iss_v, iss_ragged, iss_lds + C::TILE, w);
+        // dQ^T += K^T dS^T with dS = P (dP - Delta) in its shadow; meanwhile fetch the next step's K rows
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[b][r] = fast_exp2(__builtin_fmaf(s[b][r], c2, -lse2));
-            dkdv_interleave<2 * C::KS, 4 * C::DB / C::KS, 8>();
-            __builtin_amdgcn_sched_barrier(0);
-            dma.issue_tile(iss_v, iss_ragged, iss_lds + C::TILE, w);
-            // dQ^T += K^T dS^T with dS = P (dP - Delta) in its shadow; meanwhile fetch the next step's K rows
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dp[b][8 * st + e] *= s[b][8 * st + e];
+                const bf16x8 dsb = pack_regs(dp[b], st);
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db) dqacc[db] = mfma32(ft.a[b][st][db], dsb, dqacc[db]);
+            }
+        dq_load_A<D>(nxt, aaddr, fa);
+        dkdv_interleave<4 * C::DB, 2 * C::KS / (4 * C::DB) + 1, 6>();
+        __builtin_amdgcn_sched_barrier(0);
+        if (MASKED && lo_steps) {  // the lo parts of dS, on the K^T operands still in registers
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
+                    const bf16x8 dsl = pack_regs_lo(dp[b], st, pack_regs(dp[b], st));
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) dp[b][8 * st + e] *= s[b][8 * st + e];
-                    const bf16x8 dsb = pack_regs(dp[b], st);
-#pragma unroll
-                    for (int db = 0; db < C::DB; ++db) dqacc[db] = mfma32(ft.a[b][st][db], dsb, dqacc[db]);
+                    for (int db = 0; db < C::DB; ++db) dqacc[db] = mfma32(ft.a[b][st][db], dsl, dqacc[db]);
                 }
-            dq_load_A<D>(nxt, aaddr, fa);
-            dkdv_interleave<4 * C::DB, 2 * C::KS / (4 * C::DB) + 1, 6>();
-            __builtin_amdgcn_sched_barrier(0);
-            VA_DQ_ADVANCE()
+        }
+        stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
+    };
+    for (; j < n_plain; ++j) step(std::false_type{});
+    if constexpr (CAUSAL) {
+        for (; j < nsteps; ++j) step(std::true_type{});
+    } else {
+        // Without the causal mask the only masked step is the one holding the sample's end: it takes the
+        // simple form (the phased one with hi + lo in every such step needs more registers than there are).
+        // Its sync sits at its end: the step's own stage was published by the sync before.
+        for (; j < nsteps; ++j) {
+            dq_step<D, CAUSAL, true>(lds + stage_i * STAGE, lds + stage_i * STAGE + C::TILE, aaddr, taddr, qf, dof,
+                                     dqacc, c2, lse2, ndelta, j * BWD_STEP_KV, qrow, L, hh);
+            wait_vmcnt<PER>();
+            wg_barrier();
+            issue_all();
+            stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
         }
     }
-    for (; j < nsteps; ++j) VA_DQ_CAREFUL()
     wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
-#undef VA_DQ_SYNC
-#undef VA_DQ_ADVANCE
-#undef VA_DQ_CAREFUL
 
     if (qvalid) {
         __bf16* dqp = dQ + ((size_t)(sb + qrow) * Hq + h) * D;

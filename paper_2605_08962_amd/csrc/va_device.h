@@ -10,6 +10,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace va {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
