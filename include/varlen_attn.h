@@ -54,7 +54,8 @@ enum {
     VA_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below the *_workspace_bytes() answer */
     VA_ERR_BAD_SCALE = 5,           /* softmax_scale is NaN, infinite or negative */
     VA_ERR_HIP = 6,                 /* a HIP call failed; see varlen_attn_last_hip_error() */
-    VA_ERR_MISALIGNED = 7           /* a tensor or workspace pointer is not 16-byte aligned */
+    VA_ERR_MISALIGNED = 7,          /* a tensor or workspace pointer is not 16-byte aligned */
+    VA_ERR_BAD_CU_SEQLENS = 8       /* varlen_attn_check_cu_seqlens only: the device array breaks the precondition */
 };
 
 typedef struct {
@@ -117,6 +118,21 @@ int varlen_attn_bwd(const varlen_attn_params *p,
  */
 int varlen_attn_merge(const varlen_attn_params *p, int32_t num_parts, const void *o_parts,
                       const float *lse_parts, void *o, float *lse, void *hip_stream);
+
+/*
+ * Checks the CONTENTS of cu_seqlens, which live on the device and which no other call looks at:
+ * cu[0] = 0, cu[s] <= cu[s+1] for every sample, cu[num_seqs] = total_tokens (the precondition on a
+ * packed batch: Section 2.1, hybrid packing keeps samples apart inside one stream).  A batch that
+ * breaks it makes the attention kernels read outside the tensors.  For callers that cannot vouch
+ * for their packing code; varlen_attn_fwd / varlen_attn_bwd never call it.
+ *   workspace: at least 16 bytes of device scratch, 16-byte aligned (the verdict is written there).
+ * Unlike every other call this one SYNCHRONISES hip_stream: it copies the verdict back (4 bytes)
+ * before it returns.  It must not be called while the stream is being captured.
+ * Returns VA_OK, VA_ERR_BAD_CU_SEQLENS, or an argument error (nothing launched then).
+ * num_seqs == 0 is checked on the host: it is VA_OK exactly if total_tokens == 0.
+ */
+int varlen_attn_check_cu_seqlens(const varlen_attn_params *p, const int32_t *cu_seqlens, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *varlen_attn_status_string(int status);

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
 _lib = None
 
 VA_OK = 0
+VA_ERR_BAD_CU_SEQLENS = 8
 
 
 class VarlenAttnError(RuntimeError):
@@ -52,6 +53,8 @@ def load():
     lib.varlen_attn_bwd.restype = ctypes.c_int
     lib.varlen_attn_merge.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.varlen_attn_merge.restype = ctypes.c_int
+    lib.varlen_attn_check_cu_seqlens.argtypes = [pp, vp, vp, sz, vp]
+    lib.varlen_attn_check_cu_seqlens.restype = ctypes.c_int
     lib.varlen_attn_status_string.argtypes = [ctypes.c_int]
     lib.varlen_attn_status_string.restype = ctypes.c_char_p
     lib.varlen_attn_last_hip_error.argtypes = []
@@ -202,6 +205,19 @@ def varlen_attn_merge(o_parts, lse_parts, out=None, lse=None, stream=None):
     _check(load().varlen_attn_merge(ctypes.byref(p), P, o_parts.data_ptr(), lse_parts.data_ptr(), out.data_ptr(),
                                     lse.data_ptr(), _stream_handle(stream)))
     return out, lse
+
+
+def check_cu_seqlens(cu_seqlens, total_tokens, stream=None):
+    """True if the device array obeys cu[0] = 0, non-decreasing, cu[-1] = total_tokens.  Synchronises the stream."""
+    _require(cu_seqlens, torch.int32, "cu_seqlens")
+    p = make_params(total_tokens, cu_seqlens.numel() - 1, 1, 1, 64, False, 1.0)
+    ws = torch.empty(16, dtype=torch.uint8, device=cu_seqlens.device)
+    rc = load().varlen_attn_check_cu_seqlens(ctypes.byref(p), cu_seqlens.data_ptr(), ws.data_ptr(), ws.numel(),
+                                             _stream_handle(stream))
+    if rc == VA_ERR_BAD_CU_SEQLENS:
+        return False
+    _check(rc)
+    return True
 
 
 PARTITION_KARMARKAR_KARP = 0

@@ -224,6 +224,27 @@ int varlen_attn_merge(const varlen_attn_params* p, int32_t num_parts, const void
     return VA_OK;
 }
 
+int varlen_attn_check_cu_seqlens(const varlen_attn_params* p, const int32_t* cu_seqlens, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != VA_OK) return rc;
+    if (p->num_seqs == 0) return p->total_tokens == 0 ? VA_OK : VA_ERR_BAD_CU_SEQLENS;
+    if (!cu_seqlens || !workspace) return VA_ERR_NULL_PTR;
+    if (((uintptr_t)cu_seqlens & 3u) || !aligned16(workspace)) return VA_ERR_MISALIGNED;
+    if (workspace_bytes < 16) return VA_ERR_WORKSPACE_TOO_SMALL;
+    rc = check_device();
+    if (rc != VA_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t e = va::launch_check_cu_seqlens(cu_seqlens, p->num_seqs, p->total_tokens, (int32_t*)workspace, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    int32_t verdict = 1;
+    e = hipMemcpyAsync(&verdict, workspace, sizeof(verdict), hipMemcpyDeviceToHost, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return verdict == 0 ? VA_OK : VA_ERR_BAD_CU_SEQLENS;
+}
+
 int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q, const void* k,
                     const void* v, const void* o, const float* lse, const int32_t* cu_seqlens,
                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
@@ -298,6 +319,7 @@ const char* varlen_attn_status_string(int status) {
         case VA_ERR_BAD_SCALE: return "softmax_scale must be finite and >= 0";
         case VA_ERR_HIP: return "a HIP call failed";
         case VA_ERR_MISALIGNED: return "a tensor or workspace pointer is not 16-byte aligned";
+        case VA_ERR_BAD_CU_SEQLENS: return "cu_seqlens must start at 0, never decrease and end at total_tokens";
         default: return "unknown status";
     }
 }

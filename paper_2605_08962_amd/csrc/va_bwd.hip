@@ -607,12 +607,15 @@ hipError_t launch_dkdv_128(const BwdArgs& a, hipStream_t stream) { return launch
 // ------------------------------------------------------------------------------------------------
 // dQ
 // ------------------------------------------------------------------------------------------------
-template <int D, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned char* vt,
-                                        const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
-                                        const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
-                                        f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
-                                        int kv0, int qrow, int L, int hh, bool lo = MASKED) {
+// The step that holds the sample's end, for the kernel without the causal mask (under it the masked steps
+// run in phases, see dq_kernel): keys and rows beyond the sample are masked, dS goes through its MFMAs as
+// bf16 hi + lo.  Operands are read right before use.
+template <int D>
+__device__ __forceinline__ void dq_end_step(const unsigned char* kt, const unsigned char* vt,
+                                            const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
+                                            const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
+                                            f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
+                                            int kv0, int qrow, int L, int hh) {
     using C = BwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
     f32x16 s[2], dp[2];
@@ -633,43 +636,24 @@ __device__ __forceinline__ void dq_step(const unsigned char* kt, const unsigned 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float p = fast_exp2(__builtin_fmaf(s[b][r], c2, -lse2));
-            if (MASKED) {
-                const int kv = kv0 + 32 * b + 8 * (r / 4) + 4 * hh + (r % 4);
-                const bool ok = kv < L && qrow < L && (!CAUSAL || kv <= qrow);
-                p = ok ? p : 0.f;
-            }
+            const int kv = kv0 + 32 * b + 8 * (r / 4) + 4 * hh + (r % 4);
+            p = (kv < L && qrow < L) ? p : 0.f;
             dp[b][r] = p * (dp[b][r] + ndelta);
         }
-    constexpr bool LO_INLINE = MASKED && !CAUSAL;  // as in dkdv_step
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             const bf16x8 dsb = pack_regs(dp[b], st);
-            bf16x8 dsl;
-            if (LO_INLINE) dsl = pack_regs_lo(dp[b], st, dsb);
+            const bf16x8 dsl = pack_regs_lo(dp[b], st, dsb);
             const int rowoff = (32 * b + 16 * st) * ROWB;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
                 bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
                 dqacc[db] = mfma32(ak, dsb, dqacc[db]);
-                if (LO_INLINE) dqacc[db] = mfma32(ak, dsl, dqacc[db]);
+                dqacc[db] = mfma32(ak, dsl, dqacc[db]);
             }
         }
-    if (MASKED && CAUSAL && lo) {
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const bf16x8 dsl = pack_regs_lo(dp[b], st, pack_regs(dp[b], st));
-                const int rowoff = (32 * b + 16 * st) * ROWB;
-#pragma unroll
-                for (int db = 0; db < C::DB; ++db) {
-                    bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
-                    dqacc[db] = mfma32(ak, dsl, dqacc[db]);
-                }
-            }
-    }
 }
 
 // ---- the mask-free dQ step in phases (see the dK/dV kernel): S | dP with exp in its shadow | dQ
@@ -912,8 +896,8 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
         // simple form (the phased one with hi + lo in every such step needs more registers than there are).
         // Its sync sits at its end: the step's own stage was published by the sync before.
         for (; j < nsteps; ++j) {
-            dq_step<D, CAUSAL, true>(lds + stage_i * STAGE, lds + stage_i * STAGE + C::TILE, aaddr, taddr, qf, dof,
-                                     dqacc, c2, lse2, ndelta, j * BWD_STEP_KV, qrow, L, hh);
+            dq_end_step<D>(lds + stage_i * STAGE, lds + stage_i * STAGE + C::TILE, aaddr, taddr, qf, dof,
+                           dqacc, c2, lse2, ndelta, j * BWD_STEP_KV, qrow, L, hh);
             wait_vmcnt<PER>();
             wg_barrier();
             issue_all();

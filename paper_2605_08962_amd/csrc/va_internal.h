@@ -32,6 +32,11 @@ SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows);
 hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_rows, int partner_rows,
                             CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream);
 
+// Enqueue the check of cu_seqlens' contents: *verdict (device) = 0 if cu[0] = 0, cu never decreases and
+// cu[num_seqs] = total_tokens, else 1.
+hipError_t launch_check_cu_seqlens(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int32_t* verdict,
+                                   hipStream_t stream);
+
 struct FwdArgs {
     const void *q, *k, *v;
     void* o;

@@ -141,4 +141,21 @@ hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_ro
     return hipGetLastError();
 }
 
+// One workgroup walks cu_seqlens; every thread notes what it sees wrong, the block ORs the notes.
+__global__ void __launch_bounds__(SCHED_THREADS)
+check_cu_seqlens_kernel(const int32_t* __restrict__ cu, int B, int T, int32_t* __restrict__ verdict) {
+    int bad = 0;
+    for (int s = threadIdx.x; s < B; s += SCHED_THREADS) bad |= cu[s] > cu[s + 1];
+    if (threadIdx.x == 0) bad |= cu[0] != 0 || cu[B] != T;
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) *verdict = bad ? 1 : 0;
+}
+
+hipError_t launch_check_cu_seqlens(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int32_t* verdict,
+                                   hipStream_t stream) {
+    hipLaunchKernelGGL(check_cu_seqlens_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs,
+                       total_tokens, verdict);
+    return hipGetLastError();
+}
+
 }  // namespace va

@@ -42,8 +42,8 @@ def test_params_struct_matches_header():
 
 def test_status_strings(lib):
     from paper_2605_08962_amd import binding
-    seen = {binding.status_string(i) for i in range(8)}
-    assert len(seen) == 8 and binding.status_string(0) == "ok"
+    seen = {binding.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and binding.status_string(0) == "ok"
     assert binding.status_string(99) == "unknown status"
 
 
@@ -82,6 +82,19 @@ def test_host_side_validation_needs_no_gpu(lib):
     args[9] = None
     assert lib.varlen_attn_bwd(ctypes.byref(ok), *args, 1 << 30, None) == 1
     assert lib.varlen_attn_bwd(ctypes.byref(mk(0, 0, 2, 2, 64, 0, 0.125)), *([None] * 11), 0, None) == 0
+
+
+def test_cu_seqlens_check_validates_its_arguments_on_the_host(lib):
+    from paper_2605_08962_amd import binding
+    mk = binding.make_params
+    call = lambda p, cu=16, ws=16, n=16: lib.varlen_attn_check_cu_seqlens(ctypes.byref(p), cu, ws, n, None)
+    assert call(mk(0, 0, 1, 1, 64, 0, 1.0), None, None, 0) == 0          # no samples, no tokens: fine, no launch
+    assert call(mk(5, 0, 1, 1, 64, 0, 1.0), None, None, 0) == 8          # tokens that belong to no sample
+    ok = mk(8, 2, 1, 1, 64, 0, 1.0)
+    assert call(ok, cu=None) == 1 and call(ok, ws=None) == 1
+    assert call(ok, cu=18) == 7 and call(ok, ws=24) == 7
+    assert call(ok, n=8) == 4
+    assert call(mk(-1, 2, 1, 1, 64, 0, 1.0)) == 2
 
 
 def test_workspace_and_work_list_bounds():

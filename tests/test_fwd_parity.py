@@ -133,3 +133,25 @@ def test_empty_inputs_and_errors():
     with pytest.raises(binding.VarlenAttnError) as e:
         binding.varlen_attn_fwd(q, q, q, cu, False, 0.125, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == 4
+
+
+def test_cu_seqlens_contents_check():
+    """varlen_attn_check_cu_seqlens against the precondition it states, on arrays a packing bug would produce."""
+    from paper_2605_08962_amd import binding
+    rng = np.random.default_rng(8)
+    lengths = rng.integers(0, 300, size=5000)            # several passes of the checking workgroup, empty samples
+    cu = np.zeros(lengths.size + 1, dtype=np.int32)
+    np.cumsum(lengths, out=cu[1:])
+    T = int(cu[-1])
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    assert binding.check_cu_seqlens(dev(cu), T)
+    assert binding.check_cu_seqlens(dev([0]), 0) and binding.check_cu_seqlens(dev([0, 7]), 7)
+    assert not binding.check_cu_seqlens(dev(cu), T + 1)          # does not end at total_tokens
+    assert not binding.check_cu_seqlens(dev(cu + 1), T + 1)      # does not start at 0
+    for at in (1, 2500, 4999):                                   # one sample of negative length
+        bad = cu.copy()
+        bad[at] = bad[at + 1] + 1
+        assert not binding.check_cu_seqlens(dev(bad), T)
+    assert not binding.check_cu_seqlens(dev([0, -3, 4]), 4)
+    assert not binding.check_cu_seqlens(dev([0]), 4)
+
