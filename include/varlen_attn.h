@@ -22,7 +22,9 @@
  * is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default stream), and the
  * buffers must stay alive until the stream has run it.  Outputs are fully overwritten.  The
  * workspace is scratch; its contents mean nothing between calls, and two calls that share one
- * workspace must be ordered on one stream.
+ * workspace must be ordered on one stream.  The calls may be recorded under HIP stream capture:
+ * the work list is rebuilt on the device inside every call, so a recorded graph stays valid when
+ * the buffers' contents change, cu_seqlens included, as long as the sizes in `p` stay the same.
  *
  * Layouts (row-major, contiguous):
  *     q, o, dout, dq : bf16 [total_tokens, num_q_heads,  head_dim]
