@@ -139,6 +139,117 @@ sustained_kernel(const bf16x8* __restrict__ in, float* out, unsigned long long* 
     }
 }
 
+// Two waves per SIMD taking turns: while waves 0..3 (one per SIMD) run their MFMAs, waves 4..7 run their
+// vector work, then a workgroup barrier and the roles swap ("ping-pong").  PINGPONG = 0 runs the same
+// work without barriers, each wave interleaving VPER vector instructions after every MFMA.  Operands
+// come from memory (random data), the run is long enough for the clock to settle, and both the cycle
+// counter and the 100 MHz real-time counter are read, so that time per unit includes what the power
+// limit does to the clock.
+template <int NM, int NG, int PINGPONG, int VPER>
+__global__ void __launch_bounds__(512)
+turns_kernel(const bf16x8* __restrict__ in, float* out, unsigned long long* stamps, int iters) {
+    const int w = threadIdx.x >> 6;
+    bf16x8 a[2], b[2];
+    for (int i = 0; i < 2; i++) {
+        a[i] = in[(threadIdx.x * 4 + i) % 4096];
+        b[i] = in[(threadIdx.x * 4 + 2 + i) % 4096];
+    }
+    f32x16 c0, c1;
+    for (int r = 0; r < 16; r++) { c0[r] = 0.f; c1[r] = 0.f; }
+    float x[16];
+    for (int i = 0; i < 16; i++) x[i] = -(threadIdx.x * 0.001f + i * 0.1f) * (float)a[0][0];
+    auto mfmas = [&]() {
+#pragma unroll
+        for (int m = 0; m < NM; m += 2) {
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[(m >> 1) & 1], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[(m >> 1) & 1], c1, 0, 0, 0);
+        }
+    };
+    auto vector_work = [&]() {
+#pragma unroll
+        for (int g = 0; g < NG; g++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) x[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 0.999f, -0.001f)) * -1.5f;
+    };
+    const unsigned long long r0 = __builtin_amdgcn_s_memrealtime(), cy0 = __builtin_readcyclecounter();
+    if (PINGPONG) {
+        const bool first = w < 4;  // wave-uniform
+        for (int it = 0; it < iters; it++) {
+            if (first) mfmas(); else vector_work();
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            if (first) vector_work(); else mfmas();
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+        }
+    } else {
+        for (int it = 0; it < iters; it++) {
+            mfmas();
+            vector_work();
+#pragma unroll
+            for (int m = 0; m < NM; m++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const unsigned long long r1 = __builtin_amdgcn_s_memrealtime(), cy1 = __builtin_readcyclecounter();
+    float r = c0[0] + c1[1];
+    for (int i = 0; i < 16; i++) r += x[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+    if ((threadIdx.x & 63) == 0) {  // every wave: without barriers the two waves of a SIMD need not finish together
+        unsigned long long* st = stamps + 4 * (blockIdx.x * 8 + w);
+        st[0] = r0; st[1] = r1; st[2] = cy0; st[3] = cy1;
+    }
+}
+
+static int taking_turns(float* out) {
+    bf16x8* in;
+    unsigned long long* stamps;
+    CK(hipMalloc(&in, 4096 * 16));
+    CK(hipMalloc(&stamps, 256 * 8 * 32));
+    unsigned short* h = (unsigned short*)malloc(4096 * 16);
+    unsigned long long* hs = (unsigned long long*)malloc(256 * 8 * 32);
+    srand(1);
+    for (int i = 0; i < 4096 * 8; i++) {
+        const float v = (rand() / (float)RAND_MAX) * 4.f - 2.f;
+        unsigned int u;
+        memcpy(&u, &v, 4);
+        h[i] = (unsigned short)(u >> 16);
+    }
+    CK(hipMemcpy(in, h, 4096 * 16, hipMemcpyHostToDevice));
+    printf("\n| MFMAs per unit | vector work per unit | two waves per SIMD | cycles per unit per SIMD | shader clock GHz | ns per unit per SIMD |\n|---|---|---|---|---|---|\n");
+#define RUN3(NM, NG, PP, VPER, LABEL)                                                                         \
+    {                                                                                                         \
+        const int iters = 60000;                                                                              \
+        turns_kernel<NM, NG, PP, VPER><<<256, 512>>>(in, out, stamps, 2000);                                   \
+        CK(hipDeviceSynchronize());                                                                           \
+        turns_kernel<NM, NG, PP, VPER><<<256, 512>>>(in, out, stamps, iters);                                  \
+        CK(hipDeviceSynchronize());                                                                           \
+        CK(hipMemcpy(hs, stamps, 256 * 8 * 32, hipMemcpyDeviceToHost));                                       \
+        double rt = 0, cy = 0;                                                                                \
+        for (int i = 0; i < 256; i++) { /* per workgroup: first start to last end over its waves */           \
+            unsigned long long r0 = ~0ull, r1 = 0, c0 = ~0ull, c1 = 0;                                        \
+            for (int w = 0; w < 8; w++) {                                                                     \
+                const unsigned long long* st = hs + 4 * (i * 8 + w);                                          \
+                r0 = st[0] < r0 ? st[0] : r0; r1 = st[1] > r1 ? st[1] : r1;                                   \
+                c0 = st[2] < c0 ? st[2] : c0; c1 = st[3] > c1 ? st[3] : c1;                                   \
+            }                                                                                                 \
+            rt += (double)(r1 - r0); cy += (double)(c1 - c0);                                                 \
+        }                                                                                                     \
+        printf("| %d | %d x {fma, exp2, mul} | %s | %.0f | %.2f | %.0f |\n", NM, 16 * NG, LABEL,              \
+               cy / 256 / iters / 2, cy / rt / 10.0, rt * 10.0 / 256 / iters / 2);                            \
+    }
+    RUN3(32, 3, 0, 5, "each interleaving its own")
+    RUN3(32, 3, 1, 0, "taking turns, barrier between")
+    RUN3(24, 2, 0, 4, "each interleaving its own")
+    RUN3(24, 2, 1, 0, "taking turns, barrier between")
+    RUN3(16, 3, 0, 9, "each interleaving its own")
+    RUN3(16, 3, 1, 0, "taking turns, barrier between")
+    return 0;
+}
+
 static int sustained_mfma(float* out) {
     bf16x8* in;
     unsigned long long* stamps;
@@ -232,5 +343,6 @@ int main() {
                M ? (double)(h[1] - h[0]) / (2 * ITERS) / 16 : 0.0, V ? (double)(h[9] - h[8]) / (2 * ITERS) / 64 : 0.0); \
     }
     RUN2(0, 1, 0) RUN2(0, 0, 1) RUN2(0, 1, 1) RUN2(1, 0, 1) RUN2(1, 1, 1)
-    return sustained_mfma(out);
+    if (sustained_mfma(out)) return 1;
+    return taking_turns(out);
 }
