@@ -364,3 +364,32 @@ def test_merge_special_cases():
     ab_o, ab_lse = oracle.merge(o[:2], lse[:2])
     s_o, s_lse = oracle.merge(np.stack([ab_o.astype(np.float32), o[2]]), np.stack([ab_lse, lse[2]]))
     assert np.abs(s_o - f_o).max() < 1e-6 and np.abs(s_lse - f_lse).max() < 1e-14
+
+
+# --- the scheduler's work list (oracle/schedule.py) ---
+
+def test_schedule_costs_match_the_mask_counted_pair_by_pair():
+    from oracle import schedule
+    # partner tiles with at least one allowed (query, key) pair, for every tile of samples around the
+    # tile sizes the kernels use (row tiles of 128, partner tiles of 64) and a smaller pair of sizes
+    for R, U in ((128, 64), (8, 4)):
+        for L in [1, U - 1, U, U + 1, R - 1, R, R + 1, 2 * R, 2 * R + U + 3, 3 * R - 1]:
+            for mode in schedule.MODES:
+                items = schedule.work_items([0, L], R, U, mode)
+                assert [it[3] for it in items] == list(range(-(-L // R)))
+                for first, begin, end, t, cost in items:
+                    assert (first, begin, end) == (t * R, 0, L)
+                    assert cost == schedule.cost_by_brute_force(L, t, R, U, mode), (R, U, L, t, mode)
+
+
+def test_schedule_of_config_1_by_hand():
+    from oracle import schedule
+    cu = [0, 16, 53, 117, 246]          # lengths 16, 37, 64, 129
+    full = schedule.work_items(cu, 128, 64, "full")
+    assert full == [(0, 0, 16, 0, 1), (16, 16, 53, 0, 1), (53, 53, 117, 0, 1), (117, 117, 246, 0, 3), (245, 117, 246, 1, 3)]
+    cq = schedule.work_items(cu, 128, 64, "causal_query")
+    assert [it[4] for it in cq] == [1, 1, 1, 2, 3]      # rows 0..127 of the last sample see keys 0..127 only
+    ck = schedule.work_items(cu, 128, 64, "causal_key")
+    assert [it[4] for it in ck] == [1, 1, 1, 3, 1]      # its last key is seen by one query
+    # empty samples produce no tiles
+    assert schedule.work_items([0, 0, 5, 5], 128, 64, "full") == [(0, 0, 5, 0, 1)]
