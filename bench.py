@@ -26,9 +26,12 @@ sys.path.insert(0, ROOT)
 METRIC = "varlen attention useful TFLOP/s fwd/bwd on 1 MI355X; % of bf16 MFMA peak"
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), or None.
-# Read off profiles/bench_vit_d64_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
+# Read off profiles/bench_*_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
 # the factors being what the same counters read for a 1 GiB device copy in the same run.
 MEASURED_TRAFFIC_BYTES = {
+    ("llm_causal_gqa_d128", "dkdv"): int((2.0 * 3.51e+06 + 1.312e+05) * 1024),
+    ("llm_causal_gqa_d128", "dq"): int((2.0 * 1.001e+06 + 2.712e+05) * 1024),
+    ("llm_causal_gqa_d128", "fwd"): int((2.0 * 7.145e+05 + 2.668e+05) * 1024),
     ("long_short_mix_d80", "dkdv"): int((2.0 * 5.14e+06 + 8.147e+05) * 1024),
     ("long_short_mix_d80", "dq"): int((2.0 * 5.531e+06 + 3.923e+05) * 1024),
     ("long_short_mix_d80", "fwd"): int((2.0 * 4.851e+06 + 3.833e+05) * 1024),
