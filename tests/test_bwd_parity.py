@@ -136,3 +136,26 @@ def test_clock_probe_counts_and_leaves_results_alone():
     after = clocks.clone()
     run()  # detached: the counters must not move any more
     assert torch.equal(after, clocks)
+
+
+@pytest.mark.parametrize("D,causal", [(64, False), (128, True), (128, False)])
+def test_self_similar_inputs(D, causal):
+    # Ungraded robustness input, like the peaky one: K = Q puts a sharp diagonal into P (P_ii averages 0.67 and
+    # reaches 0.997 at D = 64, and is closer to 1 still at D = 128).  There dS_ii = P_ii (dP_ii - Delta_i) is a
+    # small difference of large terms, and Delta_i = <dO_i, O_i> is formed from the forward's O as the interface
+    # stores it, in bf16: its rounding (up to 0.04 in Delta on these inputs, oracle-side estimate) goes straight
+    # into dS_ii and from there, times K_i, into dQ_i and dK_i, while the gradients themselves all but vanish
+    # (RMS 0.02-0.15), so that errors relative to them say nothing.  No kernel arithmetic can recover what the
+    # saved O no longer holds; the case has to show that nothing worse happens, in absolute terms:
+    # max error <= 5e-2, RMS error <= 3e-3 (measured: 0.037 and 0.0019 at most).
+    import oracle
+    w = W.make_custom([700, 129, 64], 2, 2, D, causal, seed=300 + D, with_dout=True)
+    w.k = w.q.copy()
+    got = _run_bwd(w)
+    ref = oracle.bwd(w.f32("q"), w.f32("k"), w.f32("v"), w.f32("dout"), w.cu_seqlens, w.causal, w.scale)
+    for name, g_, r_ in zip(("dQ", "dK", "dV"), got, ref):
+        assert np.isfinite(g_).all()
+        err = np.abs(g_ - r_)
+        rms = float(np.sqrt((err ** 2).mean()))
+        print(f"   {name}: max_abs={err.max():.2e} rms={rms:.2e} (reference rms {np.sqrt((r_ ** 2).mean()):.2e})", flush=True)
+        assert err.max() <= 5e-2 and rms <= 3e-3, name

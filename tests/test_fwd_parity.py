@@ -155,3 +155,16 @@ def test_cu_seqlens_contents_check():
     assert not binding.check_cu_seqlens(dev([0, -3, 4]), 4)
     assert not binding.check_cu_seqlens(dev([0]), 4)
 
+
+
+@pytest.mark.parametrize("D,causal", [(64, False), (80, False), (128, True)])
+def test_self_similar_and_shifted_keys(D, causal):
+    # Structure that i.i.d. inputs never show: K = Q (every row's own key scores |q|^2 / sqrt(D), about
+    # sqrt(D), far above the N(0, 1) rest: a sharp diagonal across every tile), then the same keys moved by
+    # a common offset of 3 per channel (softmax does not change, every score does: the running maximum
+    # works against a large per-row constant).
+    w = W.make_custom([700, 129, 64], 2, 2, D, causal, seed=300 + D)
+    w.k = w.q.copy()
+    _check_full(w, allow_output_rounding=True)
+    w.k = W.f32_to_bf16_bits(W.bf16_bits_to_f32(w.q) + 3.0)
+    _check_full(w, allow_output_rounding=True)
