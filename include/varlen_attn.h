@@ -97,6 +97,10 @@ int varlen_attn_fwd(const varlen_attn_params *p,
  * Backward: writes dq, dk, dv from dout and the forward's saved o and lse (P is recomputed from
  * q, k and lse, as the paper's recomputation of core attention implies, Section 5 "Selective
  * Activation Offloading").  dk and dv are summed over the query heads that share a kv head.
+ * Two kernels, no atomics, results are bit-reproducible: dQ per query tile (it also forms
+ * Delta_i = <dout_i, o_i> from `o` as stored, in bf16, and leaves it with lse in the workspace),
+ * then dK and dV per key tile.  Rows whose softmax is nearly one-hot feel the rounding of `o`
+ * through Delta: dS = P (dP - Delta) is a small difference of large terms there.
  */
 int varlen_attn_bwd(const varlen_attn_params *p,
                     const void *dout, const void *q, const void *k, const void *v,
