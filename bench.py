@@ -75,8 +75,8 @@ def report(args, torch, binding, W, to_gpu_bf16):
     cases[2] = ("3-short", W.make_custom(short, w3.num_q_heads, w3.num_kv_heads, w3.head_dim, w3.causal,
                                          seed=w3.seed, with_dout=True, scale=w3.scale))
     print("| config | mask | B | T | Hq/Hkv | D | pass | median ms | useful TFLOP/s | % of 2.5 PFLOP/s "
-          "| min HBM GB | GB/s at min bytes |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|", flush=True)
+          "| shader clock GHz | % of the MFMA peak at that clock | min HBM GB | GB/s at min bytes |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|", flush=True)
     for name, w in cases:
         q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
         cu = torch.from_numpy(w.cu_seqlens).cuda()
@@ -105,17 +105,25 @@ def report(args, torch, binding, W, to_gpu_bf16):
                 fn()
             ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                   for _ in range(args.steps)]
+            # the clock the pass's kernels run at during the timed calls: shader cycles over 100 MHz ticks,
+            # summed over their workgroups (two clock reads and two atomics per workgroup)
+            clocks = torch.zeros(6, dtype=torch.int64, device="cuda")
+            binding.profile_clock_probe(clocks)
             for a, b in ev:
                 a.record()
                 fn()
                 b.record()
             torch.cuda.synchronize()
+            binding.profile_clock_probe(None)
             ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
             tf = flops / (ms * 1e-3) / 1e12
+            ck = clocks.cpu().tolist()
+            ghz = 0.1 * sum(ck[1::2]) / max(sum(ck[0::2]), 1)
+            peak_at_clock = 256 * 4 * 1024 * ghz * 1e-3   # TFLOP/s: CUs x SIMDs x bf16 flop per cycle x GHz
             print(f"| {name} | {'causal' if w.causal else 'full'} | {w.num_seqs} | {T} | "
                   f"{w.num_q_heads}/{w.num_kv_heads} | {w.head_dim} | {pname} | {ms:.3f} | {tf:.1f} | "
-                  f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {min_bytes[pname] / 1e9:.3f} | "
-                  f"{min_bytes[pname] / (ms * 1e-3) / 1e9:.0f} |", flush=True)
+                  f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {ghz:.2f} | {100 * tf / peak_at_clock:.1f} | "
+                  f"{min_bytes[pname] / 1e9:.3f} | {min_bytes[pname] / (ms * 1e-3) / 1e9:.0f} |", flush=True)
         del q, k, v, do, o, lse, ws_f, ws_b, dq, dk, dv
         torch.cuda.empty_cache()
 
