@@ -1,4 +1,5 @@
-"""The library under HIP graph capture: forward + backward recorded once, replayed on new data.
+"""The library under HIP graph capture (forward + backward recorded once, replayed on new data) and called
+from two host threads at once.
 
 The calls allocate nothing and never synchronise, and the scheduler runs on the device inside every
 call, so a recorded graph stays valid when the contents of the buffers change, sample boundaries
@@ -82,3 +83,50 @@ def test_recorded_forward_backward_replays_on_new_data(Hq, Hkv, D, causal):
             for name, g_, r_ in (("dQ", got[2], rdq), ("dK", got[3], rdk), ("dV", got[4], rdv)):
                 assert_close(name, to_f64(g_), r_, max_abs=2e-2 if causal else 1e-2, allow_output_rounding=True)
         print(f"   replay {replay}: identical to the eager call", flush=True)
+
+
+def test_two_host_threads_on_two_streams():
+    """The library keeps no mutable state between calls (the header says so): two host threads, each with a
+    stream, buffers and workspace of its own, call forward + backward at the same time (ctypes drops the GIL
+    around the calls) and get what serial calls give, bit for bit."""
+    import threading
+    from paper_2605_08962_amd import binding
+    cases = [(4, 4, 64, False, 11), (8, 2, 128, True, 12)]
+    B, T = 9, 2000
+    jobs = []
+    for Hq, Hkv, D, causal, seed in cases:
+        rng = np.random.default_rng(seed)
+        gen = torch.Generator(device="cuda").manual_seed(seed)
+        draw = lambda h: torch.randn((T, h, D), device="cuda", generator=gen).to(torch.bfloat16)
+        jobs.append(dict(q=draw(Hq), k=draw(Hkv), v=draw(Hkv), do=draw(Hq), cu=torch.from_numpy(_cu(rng, B, T)).cuda(),
+                         causal=causal, scale=D ** -0.5))
+
+    def run(job, stream, reps):
+        out = None
+        with torch.cuda.stream(stream):
+            for _ in range(reps):
+                o, lse = binding.varlen_attn_fwd(job["q"], job["k"], job["v"], job["cu"], job["causal"], job["scale"],
+                                                 kv_splits=1)
+                dq, dk, dv = binding.varlen_attn_bwd(job["do"], job["q"], job["k"], job["v"], o, lse, job["cu"],
+                                                     job["causal"], job["scale"])
+                out = (o, lse, dq, dk, dv)
+            stream.synchronize()
+        return out
+
+    serial = [run(job, torch.cuda.current_stream(), 1) for job in jobs]
+    torch.cuda.synchronize()
+    results = [None, None]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+
+    def worker(i):
+        results[i] = run(jobs[i], streams[i], 20)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for i in range(2):
+        for name, a, b in zip(("O", "LSE", "dQ", "dK", "dV"), results[i], serial[i]):
+            assert torch.equal(a, b), f"thread {i}: {name} differs from the serial call"
