@@ -1,4 +1,4 @@
-"""GPU parity on seeded random shapes: lengths, head counts, head_dim and mask drawn per case, forward
+"""GPU parity on 48 seeded random shapes: lengths, head counts, head_dim and mask drawn per case, forward
 and backward against the fp64 oracle.  Complements the hand-picked cases: tile boundaries, empty and
 one-token samples, GQA groups and every head_dim's LDS layout meet in combinations nobody wrote down."""
 import numpy as np
@@ -15,7 +15,25 @@ pytestmark = pytest.mark.gpu
 LOOSE_GRAD_ABS = 2e-2
 
 
+def _draw_wide(seed):
+    """Seeds from 24 on: more heads per group, lengths around every power of two up to 1025 or a few long
+    samples, and a forced number of key splits in the forward."""
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    D = int(rng.choice([64, 80, 96, 128]))
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    causal = bool(rng.integers(0, 2))
+    if rng.random() < 0.5:
+        pool = [63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025]
+        lengths = [int(rng.choice(pool)) for _ in range(int(rng.integers(1, 7)))]
+    else:
+        lengths = [int(rng.integers(1, 1800)) for _ in range(int(rng.integers(1, 4)))]
+    return lengths, Hq, Hkv, D, causal, int(rng.choice([0, 1, 2, 4]))
+
+
 def _draw(seed):
+    if seed >= 24:
+        return _draw_wide(seed)
     rng = np.random.Generator(np.random.PCG64(9000 + seed))
     D = int(rng.choice([64, 80, 96, 128]))
     Hkv = int(rng.choice([1, 2, 3]))
@@ -27,18 +45,18 @@ def _draw(seed):
     lengths = [int(rng.choice(pool)) if rng.random() < 0.6 else int(rng.integers(1, 420)) for _ in range(n)]
     if sum(lengths) == 0:
         lengths.append(5)
-    return lengths, Hq, Hkv, D, causal
+    return lengths, Hq, Hkv, D, causal, 0
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_shape_forward_and_backward(seed):
     import oracle
     from paper_2605_08962_amd import binding
-    lengths, Hq, Hkv, D, causal = _draw(seed)
-    print(f"seed={seed} lengths={lengths} Hq={Hq} Hkv={Hkv} D={D} causal={causal}", flush=True)
+    lengths, Hq, Hkv, D, causal, kv_splits = _draw(seed)
+    print(f"seed={seed} lengths={lengths} Hq={Hq} Hkv={Hkv} D={D} causal={causal} kv_splits={kv_splits}", flush=True)
     w = W.make_custom(lengths, Hq, Hkv, D, causal, seed=9100 + seed, with_dout=True)
     d = upload(w)
-    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], w.causal, w.scale)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], w.causal, w.scale, kv_splits=kv_splits)
     dq, dk, dv = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], w.causal, w.scale)
     torch.cuda.synchronize()
     q, k, v, do = w.f32("q"), w.f32("k"), w.f32("v"), w.f32("dout")
