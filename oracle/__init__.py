@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     fwd,
     fwd_rows,
     bwd,
+    bwd_q_rows,
+    bwd_kv_rows,
     merge,
     num_threads,
 )

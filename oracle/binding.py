@@ -43,6 +43,15 @@ def _load():
         lib.oracle_varlen_attn_bwd.argtypes = [f32p, f32p, f32p, f32p, i32p, ci, ci, ci, ci, ci, cd,
                                                f64p, f64p, f64p]
         lib.oracle_varlen_attn_bwd.restype = ci
+        lib.oracle_varlen_attn_bwd_saved_o.argtypes = [f32p, f32p, f32p, f32p, f64p, i32p, ci, ci, ci, ci, ci, cd,
+                                                       f64p, f64p, f64p]
+        lib.oracle_varlen_attn_bwd_saved_o.restype = ci
+        lib.oracle_varlen_attn_bwd_q_rows.argtypes = [f32p, f32p, f32p, f32p, f64p, i32p, ci, ci, ci, ci, ci, cd,
+                                                      i64p, ctypes.c_int64, f64p]
+        lib.oracle_varlen_attn_bwd_q_rows.restype = ci
+        lib.oracle_varlen_attn_bwd_kv_rows.argtypes = [f32p, f32p, f32p, f32p, f64p, i32p, ci, ci, ci, ci, ci, cd,
+                                                       ci, i64p, ctypes.c_int64, f64p, f64p]
+        lib.oracle_varlen_attn_bwd_kv_rows.restype = ci
         lib.oracle_num_threads.restype = ci
         lib.oracle_attn_merge.argtypes = [f32p, f64p, ci, ci, ci, ci, f64p, f64p]
         lib.oracle_attn_merge.restype = ci
@@ -108,23 +117,78 @@ def fwd_rows(q, k, v, cu_seqlens, causal, scale, rows):
     return o, lse
 
 
-def bwd(q, k, v, dout, cu_seqlens, causal, scale):
-    """dQ [T,Hq,D], dK, dV [T,Hkv,D] float64, from the oracle's own fp64 forward."""
+def _saved_o(o_saved, shape):
+    """The stored forward output as float64 [T,Hq,D] (a bf16 or fp32 value converts exactly), or None."""
+    if o_saved is None:
+        return None
+    o_saved = np.ascontiguousarray(o_saved, dtype=np.float64)
+    if o_saved.shape != shape:
+        raise ValueError(f"expected o_saved of shape {shape}, got {o_saved.shape}")
+    return o_saved
+
+
+def bwd(q, k, v, dout, cu_seqlens, causal, scale, o_saved=None):
+    """dQ [T,Hq,D], dK, dV [T,Hkv,D] float64, from the oracle's own fp64 forward.  With o_saved (the
+    forward output as a caller stored it, [T,Hq,D]) Delta = <dO, O> is formed from that instead of the
+    oracle's own O; everything else stays the definition."""
     lib = _load()
     cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
     q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
     dout = _f32(dout, (T, Hq, D))
+    o_saved = _saved_o(o_saved, (T, Hq, D))
     dq = np.empty((T, Hq, D), np.float64)
     dk = np.empty((T, Hkv, D), np.float64)
     dv = np.empty((T, Hkv, D), np.float64)
-    rc = lib.oracle_varlen_attn_bwd(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float),
-                                    _ptr(v, ctypes.c_float), _ptr(dout, ctypes.c_float),
-                                    _ptr(cu, ctypes.c_int32), cu.size - 1, Hq, Hkv, D,
-                                    int(bool(causal)), float(scale), _ptr(dq, ctypes.c_double),
-                                    _ptr(dk, ctypes.c_double), _ptr(dv, ctypes.c_double))
+    head = (_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float), _ptr(dout, ctypes.c_float))
+    tail = (_ptr(cu, ctypes.c_int32), cu.size - 1, Hq, Hkv, D, int(bool(causal)), float(scale),
+            _ptr(dq, ctypes.c_double), _ptr(dk, ctypes.c_double), _ptr(dv, ctypes.c_double))
+    if o_saved is None:
+        rc = lib.oracle_varlen_attn_bwd(*head, *tail)
+    else:
+        rc = lib.oracle_varlen_attn_bwd_saved_o(*head, _ptr(o_saved, ctypes.c_double), *tail)
     if rc:
         raise RuntimeError(f"oracle bwd failed with status {rc}")
     return dq, dk, dv
+
+
+def bwd_q_rows(q, k, v, dout, cu_seqlens, causal, scale, rows, o_saved=None):
+    """dQ [n,Hq,D] float64 for the listed packed query rows only (exact per row at any sample length)."""
+    lib = _load()
+    cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
+    q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
+    dout = _f32(dout, (T, Hq, D))
+    o_saved = _saved_o(o_saved, (T, Hq, D))
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    dq = np.empty((rows.size, Hq, D), np.float64)
+    rc = lib.oracle_varlen_attn_bwd_q_rows(
+        _ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float), _ptr(dout, ctypes.c_float),
+        None if o_saved is None else _ptr(o_saved, ctypes.c_double), _ptr(cu, ctypes.c_int32), cu.size - 1,
+        Hq, Hkv, D, int(bool(causal)), float(scale), _ptr(rows, ctypes.c_int64), rows.size,
+        _ptr(dq, ctypes.c_double))
+    if rc:
+        raise RuntimeError(f"oracle bwd_q_rows failed with status {rc}")
+    return dq
+
+
+def bwd_kv_rows(q, k, v, dout, cu_seqlens, causal, scale, kv_head, rows, o_saved=None):
+    """dK, dV [n,D] float64 of kv head `kv_head` for the listed packed key rows only (exact per row; the
+    statistics of every query row of the rows' samples are evaluated on the way)."""
+    lib = _load()
+    cu, T, Hq, Hkv, D = _shapes(q, k, cu_seqlens)
+    q, k, v = _f32(q, (T, Hq, D)), _f32(k, (T, Hkv, D)), _f32(v, (T, Hkv, D))
+    dout = _f32(dout, (T, Hq, D))
+    o_saved = _saved_o(o_saved, (T, Hq, D))
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    dk = np.empty((rows.size, D), np.float64)
+    dv = np.empty((rows.size, D), np.float64)
+    rc = lib.oracle_varlen_attn_bwd_kv_rows(
+        _ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float), _ptr(dout, ctypes.c_float),
+        None if o_saved is None else _ptr(o_saved, ctypes.c_double), _ptr(cu, ctypes.c_int32), cu.size - 1,
+        Hq, Hkv, D, int(bool(causal)), float(scale), int(kv_head), _ptr(rows, ctypes.c_int64), rows.size,
+        _ptr(dk, ctypes.c_double), _ptr(dv, ctypes.c_double))
+    if rc:
+        raise RuntimeError(f"oracle bwd_kv_rows failed with status {rc}")
+    return dk, dv
 
 
 def merge(o_parts, lse_parts):

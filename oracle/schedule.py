@@ -2,7 +2,7 @@
 
 The paper motivates its design with the imbalance that mixed long and short samples cause (Section
 2.2, Section 4.1.1) and picks its attention algorithm for its work partitioning on long inputs
-(Section 5, "Efficient Operators"); it gives no scheduling algorithm.  The reading taken by the
+(Section 6, "Efficient Operators"); it gives no scheduling algorithm.  The reading taken by the
 library: a packed batch is cut into row tiles of `tile_rows` rows per sample, a tile's cost is the
 number of partner tiles of `partner_rows` rows it has to visit, and tiles are handed out heaviest
 first.  This file states which tiles exist and what each costs, straight from the attention mask:

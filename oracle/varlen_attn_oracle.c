@@ -6,7 +6,7 @@
  * "cpu_baseline" leg may call it; the product path never does.  It shares no code,
  * header or table with the HIP kernels.
  *
- * What it computes.  The paper (Section 5, "Efficient Operators") adopts an exact
+ * What it computes.  The paper (Section 6, "Efficient Operators") adopts an exact
  * tiled attention algorithm for its attention layers, so the result has a plain
  * definition: scaled-dot-product softmax attention.  Samples of a packed sequence
  * never attend to each other (Section 2.1, hybrid packing, Fig. 3c); encoder
@@ -37,7 +37,8 @@
  * closed forms, length-1 sequences, packed == alone, permutation and shift
  * invariances, causal row == non-causal prefix, GQA == repeated-head MHA, central
  * finite differences, dense autograd of a library softmax, row identities, and
- * large-logit stability against extended precision.
+ * large-logit stability against extended precision; the stored-O variant against its
+ * first-order closed form, the row-subset variants against the full backward.
  */
 #include <math.h>
 #include <stdint.h>
@@ -182,14 +183,20 @@ int oracle_varlen_attn_fwd(const float *q, const float *k, const float *v, const
 
 /*
  * Backward for every row.  dq: [T, Hq, D], dk, dv: [T, Hkv, D], all double, fully
- * overwritten.  P, O and LSE are the oracle's own fp64 values (recomputed here), not
- * anything a caller saved.  Two sweeps so that every output row has one writer:
+ * overwritten.  P and LSE are the oracle's own fp64 values (recomputed here), not
+ * anything a caller saved.  Delta_i = <dO_i, O_i> uses the oracle's own fp64 O when
+ * o_saved is NULL (the definition), else the rows of o_saved: double [T, Hq, D], the
+ * forward output as a caller stored it (a training framework saves O in bf16 and the
+ * backward interface reads it back; this variant states what the exact gradient
+ * arithmetic gives from that stored O, so that the cost of the interface and the error
+ * of an implementation can be told apart).  Two sweeps so that every output row has one
+ * writer:
  *   sweep 1, per query row (i,h): LSE_i, O_i, Delta_i, dQ_i
  *   sweep 2, per key row (j,c):   dK_j, dV_j from LSE and Delta of sweep 1
  */
-int oracle_varlen_attn_bwd(const float *q, const float *k, const float *v, const float *dout,
-                           const int32_t *cu, int B, int Hq, int Hkv, int D, int causal,
-                           double scale, double *dq, double *dk, double *dv) {
+static int bwd_impl(const float *q, const float *k, const float *v, const float *dout,
+                    const double *o_saved, const int32_t *cu, int B, int Hq, int Hkv, int D,
+                    int causal, double scale, double *dq, double *dk, double *dv) {
     int rc = check_args(cu, B, Hq, Hkv, D);
     if (rc) return rc;
     const int64_t T = cu[B];
@@ -224,8 +231,9 @@ int oracle_varlen_attn_bwd(const float *q, const float *k, const float *v, const
                     const int64_t j1 = causal ? i + 1 : cu[s + 1];
                     const double l = attend_row(q, k, v, Hq, Hkv, D, scale, i, h, j0, j1, score, o_row);
                     const float *doi = dout + ((size_t)i * Hq + h) * D;
+                    const double *oi = o_saved ? o_saved + ((size_t)i * Hq + h) * D : o_row;
                     double dl = 0.0;
-                    for (int d = 0; d < D; ++d) dl += (double)doi[d] * o_row[d];
+                    for (int d = 0; d < D; ++d) dl += (double)doi[d] * oi[d];
                     lse[(size_t)h * T + i] = l;
                     delta[(size_t)h * T + i] = dl;
                     double *dqi = dq + ((size_t)i * Hq + h) * D;
@@ -274,6 +282,182 @@ int oracle_varlen_attn_bwd(const float *q, const float *k, const float *v, const
         free(score);
         free(o_row);
     }
+    free(lse);
+    free(delta);
+    return failed ? ORACLE_NO_MEM : ORACLE_OK;
+}
+
+int oracle_varlen_attn_bwd(const float *q, const float *k, const float *v, const float *dout,
+                           const int32_t *cu, int B, int Hq, int Hkv, int D, int causal,
+                           double scale, double *dq, double *dk, double *dv) {
+    return bwd_impl(q, k, v, dout, NULL, cu, B, Hq, Hkv, D, causal, scale, dq, dk, dv);
+}
+
+/* The same with Delta formed from a stored forward output o_saved (double [T, Hq, D]). */
+int oracle_varlen_attn_bwd_saved_o(const float *q, const float *k, const float *v,
+                                   const float *dout, const double *o_saved, const int32_t *cu,
+                                   int B, int Hq, int Hkv, int D, int causal, double scale,
+                                   double *dq, double *dk, double *dv) {
+    if (!o_saved) return ORACLE_BAD_ARG;
+    return bwd_impl(q, k, v, dout, o_saved, cu, B, Hq, Hkv, D, causal, scale, dq, dk, dv);
+}
+
+/*
+ * dQ for a list of packed query rows (all query heads of each listed row).  Given K and V, dQ_i
+ * depends on no other query row, so a subset of rows is exact at any sample length:
+ *     dQ[i,h,:] = scale * sum_j P_ij (dP_ij - Delta_i) K[j,c,:].
+ *   rows[n_rows] : packed row indices;  dq_rows : [n_rows, Hq, D] double
+ *   o_saved      : NULL (Delta from the oracle's own O) or double [T, Hq, D] (see bwd_impl)
+ */
+int oracle_varlen_attn_bwd_q_rows(const float *q, const float *k, const float *v,
+                                  const float *dout, const double *o_saved, const int32_t *cu,
+                                  int B, int Hq, int Hkv, int D, int causal, double scale,
+                                  const int64_t *rows, int64_t n_rows, double *dq_rows) {
+    int rc = check_args(cu, B, Hq, Hkv, D);
+    if (rc) return rc;
+    const int g = Hq / Hkv;
+    int64_t max_len = 0;
+    for (int s = 0; s < B; ++s)
+        if (cu[s + 1] - cu[s] > max_len) max_len = cu[s + 1] - cu[s];
+    for (int64_t r = 0; r < n_rows; ++r)
+        if (rows[r] < 0 || rows[r] >= cu[B]) return ORACLE_BAD_ARG;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *score = (double *)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
+        double *o_row = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!score || !o_row) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for collapse(2) schedule(dynamic, 1)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            for (int h = 0; h < Hq; ++h) {
+                if (!score || !o_row) continue;
+                const int64_t i = rows[r];
+                const int s = sample_of_row(cu, B, i);
+                const int c = h / g;
+                const int64_t j0 = cu[s];
+                const int64_t j1 = causal ? i + 1 : cu[s + 1];
+                const double l = attend_row(q, k, v, Hq, Hkv, D, scale, i, h, j0, j1, score, o_row);
+                const float *doi = dout + ((size_t)i * Hq + h) * D;
+                const double *oi = o_saved ? o_saved + ((size_t)i * Hq + h) * D : o_row;
+                double dl = 0.0;
+                for (int d = 0; d < D; ++d) dl += (double)doi[d] * oi[d];
+                double *dqi = dq_rows + ((size_t)r * Hq + h) * D;
+                for (int d = 0; d < D; ++d) dqi[d] = 0.0;
+                for (int64_t j = j0; j < j1; ++j) {
+                    const float *kj = k + ((size_t)j * Hkv + c) * D;
+                    const float *vj = v + ((size_t)j * Hkv + c) * D;
+                    const double p = exp(score[j - j0] - l);
+                    double dp = 0.0;
+                    for (int d = 0; d < D; ++d) dp += (double)doi[d] * (double)vj[d];
+                    const double ds = p * (dp - dl);
+                    for (int d = 0; d < D; ++d) dqi[d] += ds * (double)kj[d];
+                }
+                for (int d = 0; d < D; ++d) dqi[d] *= scale;
+            }
+        }
+        free(score);
+        free(o_row);
+    }
+    return failed ? ORACLE_NO_MEM : ORACLE_OK;
+}
+
+/*
+ * dK and dV for a list of packed key rows of ONE kv head c.  A key row's gradients sum over every
+ * query row of its sample (and the query heads of group c), so LSE and Delta of all those query rows
+ * are evaluated first (sweep 1, restricted to the samples that hold a listed row and to the heads of
+ * the group), then the listed key rows (sweep 2):
+ *     dV[j,c,:] = sum_{h in group c} sum_i P_ij dO[i,h,:]
+ *     dK[j,c,:] = scale * sum_{h in group c} sum_i P_ij (dP_ij - Delta_i) Q[i,h,:]
+ *   rows[n_rows] : packed row indices;  dk_rows, dv_rows : [n_rows, D] double
+ *   o_saved      : NULL or double [T, Hq, D] (see bwd_impl)
+ */
+int oracle_varlen_attn_bwd_kv_rows(const float *q, const float *k, const float *v,
+                                   const float *dout, const double *o_saved, const int32_t *cu,
+                                   int B, int Hq, int Hkv, int D, int causal, double scale, int c,
+                                   const int64_t *rows, int64_t n_rows, double *dk_rows,
+                                   double *dv_rows) {
+    int rc = check_args(cu, B, Hq, Hkv, D);
+    if (rc) return rc;
+    if (c < 0 || c >= Hkv) return ORACLE_BAD_ARG;
+    const int64_t T = cu[B];
+    const int g = Hq / Hkv;
+    int64_t max_len = 0;
+    for (int s = 0; s < B; ++s)
+        if (cu[s + 1] - cu[s] > max_len) max_len = cu[s + 1] - cu[s];
+    for (int64_t r = 0; r < n_rows; ++r)
+        if (rows[r] < 0 || rows[r] >= T) return ORACLE_BAD_ARG;
+    char *wanted = (char *)calloc((size_t)(B > 0 ? B : 1), 1); /* samples that hold a listed row */
+    double *lse = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * g);
+    double *delta = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * g);
+    if (!wanted || !lse || !delta) {
+        free(wanted);
+        free(lse);
+        free(delta);
+        return ORACLE_NO_MEM;
+    }
+    for (int64_t r = 0; r < n_rows; ++r) wanted[sample_of_row(cu, B, rows[r])] = 1;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *score = (double *)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
+        double *o_row = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!score || !o_row) {
+#pragma omp atomic write
+            failed = 1;
+        }
+        /* sweep 1: LSE and Delta, stored as [member of the group][row] */
+        for (int s = 0; s < B; ++s) {
+            if (!wanted[s]) continue;
+#pragma omp for collapse(2) schedule(dynamic, 4)
+            for (int64_t i = cu[s]; i < cu[s + 1]; ++i) {
+                for (int m = 0; m < g; ++m) {
+                    if (!score || !o_row) continue;
+                    const int h = c * g + m;
+                    const int64_t j1 = causal ? i + 1 : cu[s + 1];
+                    const double l = attend_row(q, k, v, Hq, Hkv, D, scale, i, h, cu[s], j1, score, o_row);
+                    const float *doi = dout + ((size_t)i * Hq + h) * D;
+                    const double *oi = o_saved ? o_saved + ((size_t)i * Hq + h) * D : o_row;
+                    double dl = 0.0;
+                    for (int d = 0; d < D; ++d) dl += (double)doi[d] * oi[d];
+                    lse[(size_t)m * T + i] = l;
+                    delta[(size_t)m * T + i] = dl;
+                }
+            }
+        }
+        /* sweep 2: the listed key rows */
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const int64_t j = rows[r];
+            const int s = sample_of_row(cu, B, j);
+            const float *kj = k + ((size_t)j * Hkv + c) * D;
+            const float *vj = v + ((size_t)j * Hkv + c) * D;
+            double *dkj = dk_rows + (size_t)r * D;
+            double *dvj = dv_rows + (size_t)r * D;
+            for (int d = 0; d < D; ++d) dkj[d] = dvj[d] = 0.0;
+            const int64_t i0 = causal ? j : cu[s];
+            for (int m = 0; m < g; ++m) {
+                const int h = c * g + m;
+                for (int64_t i = i0; i < cu[s + 1]; ++i) {
+                    const float *qi = q + ((size_t)i * Hq + h) * D;
+                    const float *doi = dout + ((size_t)i * Hq + h) * D;
+                    double sc = 0.0, dp = 0.0;
+                    for (int d = 0; d < D; ++d) sc += (double)qi[d] * (double)kj[d];
+                    for (int d = 0; d < D; ++d) dp += (double)doi[d] * (double)vj[d];
+                    const double p = exp(scale * sc - lse[(size_t)m * T + i]);
+                    const double ds = p * (dp - delta[(size_t)m * T + i]);
+                    for (int d = 0; d < D; ++d) dvj[d] += p * (double)doi[d];
+                    for (int d = 0; d < D; ++d) dkj[d] += ds * (double)qi[d];
+                }
+            }
+            for (int d = 0; d < D; ++d) dkj[d] *= scale;
+        }
+        free(score);
+        free(o_row);
+    }
+    free(wanted);
     free(lse);
     free(delta);
     return failed ? ORACLE_NO_MEM : ORACLE_OK;

@@ -1,6 +1,6 @@
 """Pins for the fp64 CPU oracle (CPU only).
 
-The paper prints no attention formula or worked number (Section 5, "Efficient Operators",
+The paper prints no attention formula or worked number (Section 6, "Efficient Operators",
 only names the exact tiled algorithm it adopts), so the oracle is pinned to what the
 mathematics fixes: brute force in a different evaluation order, closed forms, invariances,
 reductions to simpler calls, finite differences and a library autograd.
@@ -230,6 +230,82 @@ def test_p10_row_identities():
     assert np.abs(dk.sum(0)).max() < 1e-13
     # sum_j dV_j = sum_i dO_i because every row of P sums to one
     assert np.abs(dv.sum(0) - do.astype(np.float64).sum(0)).max() < 1e-13
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_p10b_every_row_of_dS_sums_to_zero(causal):
+    """Per row: sum_j dS_ij = 0 (because Delta_i = sum_j P_ij dP_ij and sum_j P_ij = 1).  Adding one
+    vector c to every key of a sample shifts row i of the scores by the constant q_i.c, which leaves P,
+    dP and Delta alone, so dQ_i = scale sum_j dS_ij k_j moves by scale (sum_j dS_ij) c: it must not move,
+    for every row and head separately.  dV does not move either; dK_j = scale sum_i dS_ij q_i has no k in it."""
+    w, q, k, v = _tiny(lengths=(9, 4, 1), Hq=4, Hkv=2, D=8, causal=causal, with_dout=True)
+    do = w.f32("dout")
+    # (multiples of 1/2: k + c is then exact in the float32 the oracle takes its inputs in)
+    c = (np.random.default_rng(3).integers(-4, 5, size=(1, 2, 8)) / 2.0).astype(np.float32)
+    dq, dk, dv = oracle.bwd(q, k, v, do, w.cu_seqlens, causal, w.scale)
+    dq2, dk2, dv2 = oracle.bwd(q, k + c, v, do, w.cu_seqlens, causal, w.scale)
+    assert np.abs(dq2 - dq).max() < 1e-12 and np.abs(dk2 - dk).max() < 1e-12 and np.abs(dv2 - dv).max() < 1e-12
+    assert np.abs(dq).max() > 1e-2      # (the gradients themselves are not small)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2)])
+def test_stored_o_variant(causal, Hq, Hkv):
+    """Backward with Delta formed from a forward output the caller stored.  Fed the oracle's own fp64 O
+    it is the plain backward, bit for bit.  Fed O + E it differs by exactly what the formulas say:
+    Delta_i moves by e_i = <dO_i, E_i>, dS_ij by -P_ij e_i, hence
+        dQ_i moves by -scale e_i (P K)_i       (P K is the forward's output with V := K),
+        dK_j moves by -scale sum_i P_ij e_i q_i (the dV formula with dO := -scale e_i q_i),
+        dV does not move."""
+    w, q, k, v = _tiny(lengths=(7, 1, 12), Hq=Hq, Hkv=Hkv, D=8, causal=causal, with_dout=True)
+    do, cu = w.f32("dout"), w.cu_seqlens
+    o, _ = oracle.fwd(q, k, v, cu, causal, w.scale)
+    ref = oracle.bwd(q, k, v, do, cu, causal, w.scale)
+    same = oracle.bwd(q, k, v, do, cu, causal, w.scale, o_saved=o)
+    assert all(np.array_equal(a, b) for a, b in zip(ref, same))
+    E = 0.05 * np.random.default_rng(11).standard_normal(o.shape)
+    dq, dk, dv = oracle.bwd(q, k, v, do, cu, causal, w.scale, o_saved=o + E)
+    e = (do.astype(np.float64) * E).sum(-1)                              # [T, Hq]
+    pk, _ = oracle.fwd(q, k, k, cu, causal, w.scale)                      # (P K)_i per query head
+    assert np.abs(dq - (ref[0] - w.scale * e[..., None] * pk)).max() < 1e-13
+    fake_do = (-w.scale * e[..., None] * q.astype(np.float64))
+    # the dV formula is linear in dO and only needs P: evaluate it in numpy from the brute-force P
+    T = q.shape[0]
+    sid = np.repeat(np.arange(len(cu) - 1), np.diff(cu))
+    allowed = sid[:, None] == sid[None, :]
+    if causal:
+        allowed &= np.arange(T)[None, :] <= np.arange(T)[:, None]
+    g = Hq // Hkv
+    shift = np.zeros_like(ref[1])
+    for h in range(Hq):
+        sc = np.where(allowed, np.exp(w.scale * (q[:, h].astype(np.float64) @ k[:, h // g].astype(np.float64).T)), 0.0)
+        p = sc / sc.sum(1, keepdims=True)
+        shift[:, h // g] += p.T @ fake_do[:, h]
+    assert np.abs(dk - (ref[1] + shift)).max() < 1e-13
+    assert np.array_equal(dv, ref[2])
+    assert np.abs(dq - ref[0]).max() > 1e-3 and np.abs(dk - ref[1]).max() > 1e-3   # (E was not negligible)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_row_subsets_match_the_full_backward(causal):
+    """dQ of listed query rows, and dK/dV of listed key rows of one kv head, are the full backward's rows
+    (same arithmetic, same order: bit for bit), with and without a stored O."""
+    w, q, k, v = _tiny(lengths=(6, 0, 11, 1, 3), Hq=4, Hkv=2, D=8, causal=causal, with_dout=True)
+    do, cu = w.f32("dout"), w.cu_seqlens
+    o, _ = oracle.fwd(q, k, v, cu, causal, w.scale)
+    o_st = o + 0.01 * np.random.default_rng(5).standard_normal(o.shape)
+    rows = np.array([0, 20, 5, 6, 16, 17, 18], np.int64)
+    for saved in (None, o_st):
+        dq, dk, dv = oracle.bwd(q, k, v, do, cu, causal, w.scale, o_saved=saved)
+        assert np.array_equal(oracle.bwd_q_rows(q, k, v, do, cu, causal, w.scale, rows, o_saved=saved), dq[rows])
+        for c in (0, 1):
+            dk_r, dv_r = oracle.bwd_kv_rows(q, k, v, do, cu, causal, w.scale, c, rows, o_saved=saved)
+            assert np.array_equal(dk_r, dk[rows, c]) and np.array_equal(dv_r, dv[rows, c])
+    assert oracle.bwd_q_rows(q, k, v, do, cu, causal, w.scale, np.zeros(0, np.int64)).shape == (0, 4, 8)
+    with pytest.raises(RuntimeError):
+        oracle.bwd_kv_rows(q, k, v, do, cu, causal, w.scale, 2, rows)
+    with pytest.raises(RuntimeError):
+        oracle.bwd_q_rows(q, k, v, do, cu, causal, w.scale, np.array([21], np.int64))
 
 
 def test_p11_zero_q_backward_closed_forms():

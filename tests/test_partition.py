@@ -72,6 +72,36 @@ def test_equal_counts(method):
         assert max(counts) - min(counts) <= 1 and sum(counts) == n
 
 
+def test_equal_counts_differencing_worked_examples():
+    # By hand, 2 bins, cost = length.  {10,9,7,6,4,2}: the start is one partial solution per group of 2
+    # consecutive values of the sorted order: A = (10|9), B = (7|6), C = (4|2), spreads 1, 1, 2.
+    # Round 1 merges the two of largest spread, C (2) and the earlier of the 1s, A, largest slot with
+    # smallest: (4+9 | 2+10) = (13|12).  Round 2 merges B and that: (7+12 | 6+13) = (19|19), and the
+    # stable sort keeps the order: bin 0 = {7,2,10}, bin 1 = {6,4,9}.
+    assert P.karmarkar_karp([10, 9, 7, 6, 4, 2], 2, lin=1.0, quad=0.0, equal_counts=True) == [0, 1, 0, 1, 1, 0]
+    # {10,1,1,1}: A = (10|1) from indices 0, 1 and B = (1|1) from indices 2, 3 merge to
+    # (10 + 1[index 3] | 1[index 1] + 1[index 2]) = (11|2): two samples each, where the unconstrained
+    # method leaves the 10 alone (10 | 1+1+1)
+    assert P.karmarkar_karp([10, 1, 1, 1], 2, lin=1.0, quad=0.0, equal_counts=True) == [0, 1, 1, 0]
+    assert P.karmarkar_karp([10, 1, 1, 1], 2, lin=1.0, quad=0.0) in ([0, 1, 1, 1], [1, 0, 0, 0])
+    # 3 bins, {9,8,7,6,5,4}: A = (9|8|7), B = (6|5|4); merged (9+4 | 8+5 | 7+6) = (13|13|13)
+    b = P.karmarkar_karp([9, 8, 7, 6, 5, 4], 3, lin=1.0, quad=0.0, equal_counts=True)
+    assert b == [0, 1, 2, 2, 1, 0]
+
+
+def test_equal_counts_lpt_worked_examples():
+    # By hand, 2 bins, cost = length.  {9,8,7,3,2,1}, 3 samples per bin: 9 -> bin 0 (tie: lower bin),
+    # 8 -> 1, 7 -> 1 (9 vs 8), 3 -> 0 (9 vs 15), 2 -> 0 (12 vs 15), and the 1 would go to bin 0 (14 vs 15)
+    # but bin 0 already holds its 3 samples: it goes to bin 1.  Totals 14 | 16 where the unconstrained
+    # greedy gets 15 | 15.
+    assert P.lpt([9, 8, 7, 3, 2, 1], 2, lin=1.0, quad=0.0, equal_counts=True) == [0, 1, 1, 0, 0, 1]
+    assert P.lpt([9, 8, 7, 3, 2, 1], 2, lin=1.0, quad=0.0) == [0, 1, 1, 0, 0, 0]
+    # 5 samples in 2 bins: sizes 3 and 2, and only ONE bin may take a third sample.  {10,1,1,1,1}:
+    # 10 -> 0, then 1 -> 1 three times (the third is the one allowed extra), the last 1 would again go to
+    # bin 1 (3 vs 10) but no bin may grow to 4 and no second bin to 3 ... bin 0 takes it as its 2nd.
+    assert P.lpt([10, 1, 1, 1, 1], 2, lin=1.0, quad=0.0, equal_counts=True) == [0, 1, 1, 1, 0]
+
+
 def test_result_does_not_depend_on_input_order_when_costs_are_distinct():
     vals = [3, 17, 29, 41, 58, 66, 71, 89, 97, 104, 120]
     ref = _sums(vals, P.karmarkar_karp(vals, 3, lin=1.0, quad=0.0), 3)
