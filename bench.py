@@ -230,68 +230,6 @@ def lssp(args, torch, binding, W, ranks=8, model_heads=16):
         torch.cuda.empty_cache()
 
 
-def vendor_reference(args, torch, binding):
-    """Context, not a target: this library next to PyTorch's own fused attention
-    (torch.nn.functional.scaled_dot_product_attention, its flash and memory-efficient backends) on the
-    same box, on equal-length samples (the only packed case the dense call can express: one batch row
-    per sample).  Median of HIP events over args.steps calls, forward and backward timed separately."""
-    import torch.nn.functional as F
-    from torch.nn.attention import SDPBackend, sdpa_kernel
-
-    def med(fn, reps):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); fn(); e1.record(); torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1))
-        return float(np.median(ts))
-
-    print(f"torch {torch.__version__}, HIP {torch.version.hip}\n")
-    print("| D | L | samples | Hq/Hkv | mask | pass | this library ms | TFLOP/s | torch flash ms | TFLOP/s | "
-          "torch mem-efficient ms | TFLOP/s |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
-    for D, L, B, H, causal in ((64, 16384, 2, 16, False), (80, 16384, 2, 16, False), (128, 16384, 2, 16, False),
-                               (128, 8192, 4, 32, True), (64, 2048, 32, 16, False)):
-        T = L * B
-        g = torch.Generator(device="cuda"); g.manual_seed(D + L)
-        q, k, v, do = (torch.randn((T, H, D), device="cuda", dtype=torch.bfloat16, generator=g) for _ in range(4))
-        cu = torch.arange(0, T + 1, L, dtype=torch.int32, device="cuda")
-        scale = D ** -0.5
-        flops = 4.0 * D * H * B * (L * (L + 1) / 2 if causal else L * L)
-        o, lse = binding.varlen_attn_fwd(q, k, v, cu, causal, scale)
-        ours = {"fwd": med(lambda: binding.varlen_attn_fwd(q, k, v, cu, causal, scale, out=o, lse=lse), args.steps),
-                "bwd": med(lambda: binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, causal, scale), args.steps)}
-        # [T, H, D] -> [B, H, L, D] views of the same values
-        qd, kd, vd = (x.view(B, L, H, D).transpose(1, 2).contiguous().requires_grad_(True) for x in (q, k, v))
-        dod = do.view(B, L, H, D).transpose(1, 2).contiguous()
-        theirs = {}
-        for name, be in (("flash", SDPBackend.FLASH_ATTENTION), ("efficient", SDPBackend.EFFICIENT_ATTENTION)):
-            try:
-                with sdpa_kernel(be):
-                    od = F.scaled_dot_product_attention(qd, kd, vd, is_causal=causal, scale=scale)
-                    err = float((od.detach().transpose(1, 2).reshape(T, H, D).float() - o.float()).abs().max())
-                    assert err < 5e-2, f"results differ by {err}"
-                    tf = med(lambda: F.scaled_dot_product_attention(qd, kd, vd, is_causal=causal, scale=scale), args.steps)
-                    tfb = med(lambda: F.scaled_dot_product_attention(qd, kd, vd, is_causal=causal, scale=scale).backward(dod),
-                              args.steps)
-                    theirs[name] = {"fwd": tf, "bwd": max(tfb - tf, 1e-9)}
-            except Exception as ex:  # a backend this build of torch lacks for the shape
-                sys.stderr.write(f"torch {name} backend, D={D}: {str(ex)[:120]}\n")
-                theirs[name] = None
-        for ps, mult in (("fwd", 1.0), ("bwd", 2.5)):
-            cells = [f"{ours[ps]:.3f}", f"{mult * flops / ours[ps] / 1e9:.0f}"]
-            for name in ("flash", "efficient"):
-                t = theirs[name]
-                cells += ["n/a", "n/a"] if t is None else [f"{t[ps]:.3f}", f"{mult * flops / t[ps] / 1e9:.0f}"]
-            print(f"| {D} | {L} | {B} | {H}/{H} | {'causal' if causal else 'full'} | {ps} | " + " | ".join(cells) + " |",
-                  flush=True)
-        del q, k, v, do, qd, kd, vd, dod, o, lse
-        torch.cuda.empty_cache()
-
-
 def short_regime(args, torch, binding):
     """The short-sequence regime: equal-length samples of 64..2048 tokens (about 84k tokens per batch, 16
     heads), forward and backward, as HBM GB/s at the minimum bytes (every input read once, every output
@@ -412,9 +350,6 @@ def main():
     ap.add_argument("--short-regime", action="store_true",
                     help="equal-length samples of 64..2048 tokens: HBM GB/s at the minimum bytes and useful "
                          "TFLOP/s, forward and backward; prints a markdown table")
-    ap.add_argument("--vendor-reference", action="store_true",
-                    help="context: time this library and PyTorch's own fused attention on the same box on "
-                         "equal-length samples; prints a markdown table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
@@ -443,9 +378,6 @@ def main():
         return
     if args.small_launch:
         small_launch(args, torch, binding, W)
-        return
-    if args.vendor_reference:
-        vendor_reference(args, torch, binding)
         return
     if args.short_regime:
         short_regime(args, torch, binding)

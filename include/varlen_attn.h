@@ -6,7 +6,7 @@
  * 2.1, hybrid packing, Fig. 3c).  Encoder (ViT) attention is full inside a sample (Section 2.2;
  * Section 4.1.1: the Ulysses state keeps full attention per rank), LLM attention is causal
  * (Section 4.1.1, parallelism selection rationale), and the attention layers use an exact tiled
- * algorithm (Section 5, "Efficient Operators").  The paper prints no formula; the library
+ * algorithm (Section 6, "Efficient Operators").  The paper prints no formula; the library
  * computes the textbook one.  For sample s with rows [cu[s], cu[s+1]), query head h and kv head
  * c = h / (Hq / Hkv):
  *
@@ -32,7 +32,9 @@
  *     lse            : fp32 [num_q_heads, total_tokens]
  *     cu_seqlens     : int32 [num_seqs + 1], cu[0] = 0, non-decreasing, cu[num_seqs] = total_tokens
  * Empty samples (cu[s] == cu[s+1]) are legal.  The contents of cu_seqlens live on the device and
- * are NOT validated; violating the precondition above is undefined behaviour.
+ * are NOT validated.  The scheduler clamps every sample to rows inside [0, total_tokens) and the
+ * work list to the size the workspace holds, so an array that breaks the precondition gives
+ * meaningless results but no access outside the tensors; varlen_attn_check_cu_seqlens tells.
  *
  * Errors.  Every argument the host can see is validated before anything is launched; on error
  * nothing has been enqueued.  total_tokens == 0 or num_seqs == 0 returns VA_OK with no launch.
@@ -51,7 +53,7 @@ enum {
     VA_OK = 0,
     VA_ERR_NULL_PTR = 1,            /* a required pointer is NULL */
     VA_ERR_BAD_SHAPE = 2,           /* negative size or count, heads < 1, Hq % Hkv != 0, causal not 0/1,
-                                       kv_splits or num_parts out of range */
+                                       max_seqlen < 0, kv_splits or num_parts out of range */
     VA_ERR_UNSUPPORTED = 3,         /* head_dim not in {64, 80, 96, 128}, or device is not gfx950 */
     VA_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below the *_workspace_bytes() answer */
     VA_ERR_BAD_SCALE = 5,           /* softmax_scale is NaN, infinite or negative */
@@ -68,8 +70,14 @@ typedef struct {
     int32_t head_dim;      /* D in {64, 80, 96, 128} */
     int32_t causal;        /* 0: full attention inside a sample; 1: j <= i inside a sample */
     float softmax_scale;   /* finite, >= 0 (0 is legal: uniform attention) */
-    int32_t kv_splits;     /* forward only, a tuning hint that never changes results beyond rounding:
-                              0 = automatic, 1 = never split, 2..VA_MAX_KV_SPLITS = that many
+    int32_t max_seqlen;    /* optional hint, 0 = unknown: the caller's promise that no sample is longer than
+                              this.  The work list is built on the device from cu_seqlens, so nothing is
+                              sized by it and a wrong value never makes a result wrong; the host uses it
+                              where it must decide before the device has seen the lengths: the automatic
+                              kv_splits choice, and the tile shape for batches of short samples only
+                              (see varlen_attn_fwd).  Must be >= 0. */
+    int32_t kv_splits;     /* an extension, forward only; a tuning hint that never changes results beyond
+                              rounding: 0 = automatic, 1 = never split, 2..VA_MAX_KV_SPLITS = that many
                               workgroups share the keys of each query tile (see varlen_attn_fwd) */
 } varlen_attn_params;
 enum { VA_MAX_KV_SPLITS = 8, VA_MAX_MERGE_PARTS = 64 };
@@ -95,7 +103,7 @@ int varlen_attn_fwd(const varlen_attn_params *p,
 
 /*
  * Backward: writes dq, dk, dv from dout and the forward's saved o and lse (P is recomputed from
- * q, k and lse, as the paper's recomputation of core attention implies, Section 5 "Selective
+ * q, k and lse, as the paper's recomputation of core attention implies, Section 6 "Selective
  * Activation Offloading").  dk and dv are summed over the query heads that share a kv head.
  * Two kernels, no atomics, results are bit-reproducible: dQ per query tile (it also forms
  * Delta_i = <dout_i, o_i> from `o` as stored, in bf16, and leaves it with lse in the workspace),
@@ -154,6 +162,22 @@ int varlen_attn_last_hip_error(void);
 int64_t varlen_attn_max_work_items(const varlen_attn_params *p, int which);
 
 /*
+ * The scheduler's work list (Section 2.2 and 4.1.1: mixed long and short samples; Section 6, "Efficient
+ * Operators": work partitioning) computed on the HOST from a host copy of cu_seqlens, with the arithmetic
+ * the device scheduler uses: per sample the rows [begin, end) clamped into [0, total_tokens), tiles of 128
+ * rows, a tile's cost = the number of 64-row partner tiles it visits, heaviest first (equal costs in
+ * sample-then-tile order here; the device list may order them differently), at most
+ * varlen_attn_max_work_items() tiles.  For tests and for callers that want to inspect the balance; the
+ * compute calls never use it.
+ *   which            0 forward query tiles, 1 backward key tiles (dK/dV), 2 backward query tiles (dQ)
+ *   cu_seqlens_host  HOST int32 [num_seqs + 1]; need NOT obey the precondition (that is the point of the clamp)
+ *   items            HOST int32 [items_capacity][4] (out): first row, sample begin, sample end, tile index
+ * Returns the number of tiles written, or -1 on bad arguments (items_capacity below max_work_items included).
+ */
+int64_t varlen_attn_schedule_host(const varlen_attn_params *p, int which, const int32_t *cu_seqlens_host,
+                                  int32_t *items, int64_t items_capacity);
+
+/*
  * Length-balanced partition of a group's samples into `bins` subsets (one per rank): the step in
  * front of the attention kernels in the paper's pipeline (Section 5.1, decentralized grouped
  * reordering: after the sample sizes of a group of ranks are gathered, the samples are reordered
@@ -188,10 +212,10 @@ int varlen_attn_balance_partition(const int32_t *lengths, int32_t num_seqs, int3
 enum {
     VA_KERNEL_SCHED = 0, /* tile scheduler (1 launch per forward, 2 per backward) */
     VA_KERNEL_FWD = 1,   /* forward attention */
-    VA_KERNEL_DELTA = 2, /* unused (kept for numbering): Delta = rowsum(dO * O) is computed inside the dQ kernel */
-    VA_KERNEL_DKDV = 3,  /* backward: dK, dV */
-    VA_KERNEL_DQ = 4,    /* backward: dQ (also writes the per-row statistics dK/dV reads; launched first) */
-    VA_KERNEL_MERGE = 5  /* merge of partial results (varlen_attn_merge, split forward) */
+    VA_KERNEL_DKDV = 2,  /* backward: dK, dV */
+    VA_KERNEL_DQ = 3,    /* backward: dQ (also forms Delta = rowsum(dO * O) and writes the per-row statistics
+                            dK/dV reads; launched first) */
+    VA_KERNEL_MERGE = 4  /* merge of partial results (varlen_attn_merge, split forward) */
 };
 int varlen_attn_profile_enable(int on);
 int varlen_attn_profile_read(int kernel, double *total_ms, int64_t *launches);

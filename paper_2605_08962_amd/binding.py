@@ -27,7 +27,7 @@ class Params(ctypes.Structure):
     _fields_ = [("total_tokens", ctypes.c_int32), ("num_seqs", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("causal", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float), ("kv_splits", ctypes.c_int32)]
+                ("softmax_scale", ctypes.c_float), ("max_seqlen", ctypes.c_int32), ("kv_splits", ctypes.c_int32)]
 
 
 def load():
@@ -85,14 +85,15 @@ def _check(status):
         raise VarlenAttnError(status, msg)
 
 
-def make_params(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, causal, softmax_scale, kv_splits=0):
+def make_params(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, causal, softmax_scale, kv_splits=0,
+                max_seqlen=0):
     return Params(int(total_tokens), int(num_seqs), int(num_q_heads), int(num_kv_heads), int(head_dim),
-                  int(bool(causal)), float(softmax_scale), int(kv_splits))
+                  int(bool(causal)), float(softmax_scale), int(max_seqlen), int(kv_splits))
 
 
-def _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits=0):
+def _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits=0, max_seqlen=0):
     T, Hq, D = q.shape
-    return make_params(T, cu_seqlens.numel() - 1, Hq, k.shape[1], D, causal, softmax_scale, kv_splits)
+    return make_params(T, cu_seqlens.numel() - 1, Hq, k.shape[1], D, causal, softmax_scale, kv_splits, max_seqlen)
 
 
 def _require(t, dtype, name):
@@ -118,14 +119,15 @@ def _stream_handle(stream):
 
 
 def varlen_attn_fwd(q, k, v, cu_seqlens, causal, softmax_scale, out=None, lse=None, workspace=None,
-                    stream=None, kv_splits=0):
+                    stream=None, kv_splits=0, max_seqlen=0):
     """O bf16 [T,Hq,D] and LSE fp32 [Hq,T] of packed attention; asynchronous on the stream.
-    kv_splits: 0 automatic, 1 never, 2..8 workgroups sharing the keys of each query tile."""
+    kv_splits: 0 automatic, 1 never, 2..8 workgroups sharing the keys of each query tile.
+    max_seqlen: 0 unknown, else the caller's promise that no sample is longer (a hint)."""
     lib = load()
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
         _require(t, torch.bfloat16, n)
     _require(cu_seqlens, torch.int32, "cu_seqlens")
-    p = _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits)
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits, max_seqlen)
     if k.shape != v.shape or k.shape[0] != q.shape[0] or k.shape[2] != q.shape[2]:
         raise ValueError("k and v must be [T, Hkv, D] matching q's T and D")
     if out is None:
@@ -142,14 +144,14 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, causal, softmax_scale, out=None, lse=No
 
 
 def varlen_attn_bwd(dout, q, k, v, out, lse, cu_seqlens, causal, softmax_scale, dq=None, dk=None,
-                    dv=None, workspace=None, stream=None):
+                    dv=None, workspace=None, stream=None, max_seqlen=0):
     """dQ, dK, dV (bf16) from dO and the forward's saved O and LSE; asynchronous on the stream."""
     lib = load()
     for t, n in ((dout, "dout"), (q, "q"), (k, "k"), (v, "v"), (out, "out")):
         _require(t, torch.bfloat16, n)
     _require(lse, torch.float32, "lse")
     _require(cu_seqlens, torch.int32, "cu_seqlens")
-    p = _params_of(q, k, cu_seqlens, causal, softmax_scale)
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale, 0, max_seqlen)
     if dout.shape != q.shape or out.shape != q.shape or k.shape != v.shape:
         raise ValueError("dout and out must match q; k must match v")
     dq = torch.empty_like(q) if dq is None else dq
@@ -165,7 +167,7 @@ def varlen_attn_bwd(dout, q, k, v, out, lse, cu_seqlens, causal, softmax_scale, 
     return dq, dk, dv
 
 
-KERNELS = {"sched": 0, "fwd": 1, "delta": 2, "dkdv": 3, "dq": 4, "merge": 5}
+KERNELS = {"sched": 0, "fwd": 1, "dkdv": 2, "dq": 3, "merge": 4}
 
 
 def profile_enable(on=True):

@@ -60,8 +60,8 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 int check_params(const varlen_attn_params* p) {
     if (!p) return VA_ERR_NULL_PTR;
     if (p->total_tokens < 0 || p->num_seqs < 0 || p->num_q_heads < 1 || p->num_kv_heads < 1 ||
-        p->num_q_heads % p->num_kv_heads != 0 || (p->causal != 0 && p->causal != 1) || p->kv_splits < 0 ||
-        p->kv_splits > VA_MAX_KV_SPLITS)
+        p->num_q_heads % p->num_kv_heads != 0 || (p->causal != 0 && p->causal != 1) || p->max_seqlen < 0 ||
+        p->kv_splits < 0 || p->kv_splits > VA_MAX_KV_SPLITS)
         return VA_ERR_BAD_SHAPE;
     if (p->head_dim != 64 && p->head_dim != 80 && p->head_dim != 96 && p->head_dim != 128)
         return VA_ERR_UNSUPPORTED;
@@ -90,12 +90,14 @@ int check_device() {
 
 // How many workgroups share the keys of one query tile in the forward.  Splitting only pays when the
 // launch cannot fill the chip: fewer workgroups than the 256 CUs can hold at once (3 per CU at
-// head_dim <= 80, else 2), and samples long enough that every chunk still gets two key tiles.
+// head_dim <= 80, else 2), and samples long enough that every chunk still gets two key tiles (judged by
+// the caller's max_seqlen if it gave one, else by the average sample).
 int fwd_kv_splits(const varlen_attn_params* p) {
     if (p->kv_splits >= 1) return p->kv_splits;
     const int64_t wgs = ((int64_t)p->total_tokens / va::FWD_TILE_Q + p->num_seqs) * p->num_q_heads;
     const int64_t slots = 256 * (p->head_dim <= 80 ? 3 : 2);
-    const int64_t tiles_per_sample = (int64_t)p->total_tokens / p->num_seqs / va::FWD_TILE_KV;
+    const int64_t sample_len = p->max_seqlen > 0 ? std::min(p->max_seqlen, p->total_tokens) : p->total_tokens / p->num_seqs;
+    const int64_t tiles_per_sample = sample_len / va::FWD_TILE_KV;
     int64_t s = std::min<int64_t>(std::min<int64_t>(slots / std::max<int64_t>(wgs, 1), tiles_per_sample / 2), VA_MAX_KV_SPLITS);
     return (int)std::max<int64_t>(s, 1);
 }
@@ -156,6 +158,19 @@ int64_t varlen_attn_max_work_items(const varlen_attn_params* p, int which) {
     return va::sched_layout(p->total_tokens, p->num_seqs, rows).max_items;
 }
 
+int64_t varlen_attn_schedule_host(const varlen_attn_params* p, int which, const int32_t* cu_seqlens_host,
+                                  int32_t* items, int64_t items_capacity) {
+    if (check_params(p) != VA_OK || which < 0 || which > 2 || !cu_seqlens_host || !items) return -1;
+    const int rows = which == 0 ? va::FWD_TILE_Q : which == 1 ? va::BWD_TILE_KV : va::BWD_TILE_Q;
+    const int partner = which == 0 ? va::FWD_TILE_KV : which == 1 ? va::BWD_STEP_Q : va::BWD_STEP_KV;
+    const va::CostMode mode = !p->causal ? va::COST_FULL : which == 1 ? va::COST_CAUSAL_KEY : va::COST_CAUSAL_QUERY;
+    const int64_t max_items = va::sched_layout(p->total_tokens, p->num_seqs, rows).max_items;
+    if (items_capacity < max_items) return -1;
+    static_assert(sizeof(va::WorkItem) == 4 * sizeof(int32_t), "work items are four int32");
+    return va::schedule_on_host(cu_seqlens_host, p->num_seqs, p->total_tokens, rows, partner, mode, max_items,
+                                (va::WorkItem*)items);
+}
+
 int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, const void* v,
                     const int32_t* cu_seqlens, void* o, float* lse, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
@@ -176,7 +191,7 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     hipError_t e;
     {
         ProfScope ps(VA_KERNEL_SCHED, stream);
-        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::FWD_TILE_Q, va::FWD_TILE_KV,
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, p->total_tokens, va::FWD_TILE_Q, va::FWD_TILE_KV,
                                  p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, workspace, lay, stream);
     }
     if (e != hipSuccess) return hip_fail(e);
@@ -268,14 +283,14 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     hipError_t e;
     {
         ProfScope ps(VA_KERNEL_SCHED, stream);
-        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_KV, va::BWD_STEP_Q,
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, p->total_tokens, va::BWD_TILE_KV, va::BWD_STEP_Q,
                                  p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL, ws + lay.kv_ofs, lay.kv,
                                  stream);
     }
     if (e != hipSuccess) return hip_fail(e);
     {
         ProfScope ps(VA_KERNEL_SCHED, stream);
-        e = va::launch_scheduler(cu_seqlens, p->num_seqs, va::BWD_TILE_Q, va::BWD_STEP_KV,
+        e = va::launch_scheduler(cu_seqlens, p->num_seqs, p->total_tokens, va::BWD_TILE_Q, va::BWD_STEP_KV,
                                  p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q,
                                  stream);
     }

@@ -1,5 +1,5 @@
 // Backward kernels.  P is recomputed from Q, K and the saved LSE (the paper recomputes core
-// attention in the backward pass, Section 5 "Selective Activation Offloading").
+// attention in the backward pass, Section 6 "Selective Activation Offloading").
 //
 //   (row statistics: per (head, row) LSE * log2(e) and -Delta = -sum_d dO * O; every dQ workgroup
 //    computes them for its own 128 rows while it loads its fragments and writes them to the workspace,
@@ -32,17 +32,6 @@
 namespace va {
 hipError_t launch_dkdv_128(const BwdArgs& a, hipStream_t stream);  // part 1
 hipError_t launch_dq_128(const BwdArgs& a, hipStream_t stream);    // part 2
-
-#ifdef VA_PHASE_CLOCKS
-static __device__ unsigned long long g_phase[16];
-// Time stamps are only taken (scalar memory clock reads) where VA_CLK stands and are consumed by
-// VA_CLK_ACCUM once per step, so that waiting for them does not serialise the phases they separate.
-#define VA_CLK(i) tm[i] = __builtin_readcyclecounter();
-#define VA_CLK_ACCUM(n) { _Pragma("unroll") for (int i_ = 0; i_ < (n); ++i_) clk[i_] += tm[i_ + 1] - tm[i_]; }
-#else
-#define VA_CLK(i)
-#define VA_CLK_ACCUM(n)
-#endif
 
 template <int D>
 struct BwdCfg {
@@ -442,16 +431,9 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     // issued one sync earlier, may stay in flight), passes the barrier, after which every wave is done
     // with stage idx - 1, and refills that stage with step idx + NST - 1.
     int stage_i = 0;  // stage of the current step ("idx" in the comment above)
-#ifdef VA_PHASE_CLOCKS
-    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tm[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const long long tstart = __builtin_readcyclecounter();
-    unsigned long long nplain = 0;
-#endif
 #define VA_DKDV_SYNC()                                                               \
         wait_vmcnt<(NST - 3) * PER>();                                                   \
-        VA_CLK(1)                                                                        \
-        wg_barrier();                                                                    \
-        VA_CLK(2)
+        wg_barrier();
 #define VA_DKDV_ADVANCE()                                                            \
         stage_i = stage_i == NST - 1 ? 0 : stage_i + 1;
 #define VA_DKDV_CAREFUL(st)                                                          \
@@ -478,7 +460,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     float lv[16];
     bf16x8 pb[2], dsb[2];
     auto phased = [&]() {
-        VA_CLK(0)
         VA_DKDV_SYNC()
         const unsigned char* cur = lds + stage_i * STAGE;
         const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
@@ -489,7 +470,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         __builtin_amdgcn_sched_barrier(0);
         VA_DKDV_ISSUE_SLOT(0)
         VA_DKDV_ISSUE_SLOT(1)
-        VA_CLK(3)
         dkdv_load_C<D, 0>(cur, taddr, fc);
         dkdv_run_dP<D>(fa, vf, dpa);
         dkdv_run_B(s, dpa, lv, c2, pb, dsb);
@@ -499,14 +479,12 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
         __builtin_amdgcn_sched_barrier(0);
         VA_DKDV_ISSUE_SLOT(2)
-        VA_CLK(4)
         // half 1
         dkdv_load_lse<D, 1>(cur, lv, hh);
         dkdv_run_S<D>(fa, kf, s);
         __builtin_amdgcn_sched_barrier(0);
         VA_DKDV_ISSUE_SLOT(3)
         VA_DKDV_ISSUE_SLOT(4)
-        VA_CLK(5)
         dkdv_load_C<D, 1>(cur, taddr, fc);
         dkdv_run_dP<D>(fa, vf, dpb);
         dkdv_run_B(s, dpb, lv, c2, pb, dsb);
@@ -516,11 +494,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         dkdv_interleave<4 * C::DB, 2, 2>();                // dV, dK; next half's S/dP operand reads; dS
         __builtin_amdgcn_sched_barrier(0);
         VA_DKDV_ISSUE_SLOT(5)
-        VA_CLK(6)
-#ifdef VA_PHASE_CLOCKS
-        VA_CLK_ACCUM(6)
-        ++nplain;
-#endif
         VA_DKDV_ADVANCE()
     };
 
@@ -535,15 +508,6 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         }
         for (; st < nsteps; ++st) VA_DKDV_CAREFUL(st)
     }
-#ifdef VA_PHASE_CLOCKS
-    if (tid == 0) {
-        for (int i = 0; i < 7; ++i) atomicAdd(&g_phase[i], (unsigned long long)clk[i]);
-        atomicAdd(&g_phase[7], (unsigned long long)(__builtin_readcyclecounter() - tstart));
-        atomicAdd(&g_phase[8], 1ull);
-        atomicAdd(&g_phase[9], (unsigned long long)total);
-        atomicAdd(&g_phase[10], nplain);
-    }
-#endif
     wait_vmcnt<0>();  // the surplus loads issued near the end must land before this LDS is given away
 #undef VA_DKDV_SYNC
 #undef VA_DKDV_ISSUE_SLOT
@@ -953,13 +917,6 @@ hipError_t launch_bwd_dq(const BwdArgs& a, hipStream_t stream) {
         case 128: return launch_dq_128(a, stream);
         default: return hipErrorInvalidValue;
     }
-}
-#endif
-
-#if defined(VA_PHASE_CLOCKS) && VA_BWD_PART == VA_PHASE_CLOCKS - 1
-extern "C" int varlen_attn_debug_phase(unsigned long long* out, int reset) {
-    if (reset) { unsigned long long z[16] = {}; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z)); }
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase), 16 * sizeof(unsigned long long));
 }
 #endif
 

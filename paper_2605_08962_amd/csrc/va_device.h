@@ -146,7 +146,8 @@ struct LdsTile<80> {
 // serialise the prefetch with the compute).  The price is that completion must be waited for by
 // hand (wait_vmcnt) before the barrier that publishes the tile.
 // (readfirstlane of a value the compiler already knows to be uniform folds away; it is there for the
-// cases it cannot prove, because an "s" operand must never be handed a vector register)
+// cases it cannot prove, because an "s" operand must never be handed a vector register.  The statements
+// name M0 as clobbered: they overwrite it, and the compiler may keep a value of its own there.)
 __device__ __forceinline__ uint64_t uniform_u64(const void* p) {
     const uint64_t b = (uint64_t)(uintptr_t)p;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
@@ -155,7 +156,7 @@ __device__ __forceinline__ uint64_t uniform_u64(const void* p) {
 }
 __device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory");
+                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory", "m0");
 }
 // The same load for the lanes named in `lanes` only (a wave-uniform bit mask).  The execution mask is
 // narrowed inside the assembly statement and put back behind the load, so that the compiler sees no
@@ -168,12 +169,12 @@ __device__ __forceinline__ void dma16_lanes(const void* base, uint32_t byte_off,
                  : "=&s"(saved)
                  : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)),
                    "s"(lanes)
-                 : "memory");
+                 : "memory", "m0");
 }
 // Same with 4 bytes per lane: lane i's dword lands at lds_addr + 4 * i.
 __device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
-                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory");
+                 : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(byte_off), "s"(uniform_u64(base)) : "memory", "m0");
 }
 // LDS byte address (what M0 and ds instructions use) of a pointer into a __shared__ array.
 __device__ __forceinline__ uint32_t lds_address(const void* p) {

@@ -28,9 +28,31 @@ struct SchedLayout {
 };
 SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows);
 
+// Rows [begin, end) of a sample, from cu[s] and cu[s+1] as they stand on the device.  For a well-formed
+// cu_seqlens this changes nothing; for one that breaks the precondition it keeps every work item inside
+// [0, T), so that the attention kernels never address memory outside the tensors.
+__host__ __device__ inline void sched_sample_rows(int cu_s, int cu_s1, int T, int& begin, int& end) {
+    begin = cu_s < 0 ? 0 : (cu_s > T ? T : cu_s);
+    end = cu_s1 < begin ? begin : (cu_s1 > T ? T : cu_s1);
+}
+constexpr int SCHED_BINS = 4096;  // cost classes of the counting sort; costs above SCHED_BINS-1 share the top one
+// Cost of tile t (R rows) of a sample of L rows: the number of partner tiles of U rows it visits.
+__host__ __device__ inline int sched_tile_cost(int L, int t, int R, int U, int mode) {
+    int span;
+    if (mode == COST_FULL) span = L;
+    else if (mode == COST_CAUSAL_QUERY) span = L < (t + 1) * R ? L : (t + 1) * R;
+    else span = L - t * R;
+    const int c = (span + U - 1) / U;
+    return c < SCHED_BINS - 1 ? c : SCHED_BINS - 1;
+}
+// The same work list on the host (cu_seqlens in host memory): every tile once, by decreasing cost, tiles of
+// equal cost in (sample, tile) order.  items holds max_items entries; returns the number written.
+int64_t schedule_on_host(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows, int partner_rows,
+                         CostMode mode, int64_t max_items, WorkItem* items);
+
 // Enqueue the scheduler: fills header, tile offsets and the cost-sorted work list at `ws`.
-hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_rows, int partner_rows,
-                            CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream);
+hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows,
+                            int partner_rows, CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream);
 
 // Enqueue the check of cu_seqlens' contents: *verdict (device) = 0 if cu[0] = 0, cu never decreases and
 // cu[num_seqs] = total_tokens, else 1.

@@ -2,19 +2,20 @@
 //
 // The paper's motivation is the imbalance that mixed long and short samples cause (Section 2.2,
 // Section 4.1.1) and it picks its attention algorithm for its work partitioning on long inputs
-// (Section 5, "Efficient Operators").  On one GPU the same problem shows up inside a single
+// (Section 6, "Efficient Operators").  On one GPU the same problem shows up inside a single
 // launch: a 64k-token sample packed with hundreds of short ones.  This kernel turns cu_seqlens
 // into a list of row tiles sorted by decreasing cost (the number of partner tiles a tile loops
 // over), entirely on the device.  The compute kernels launch one workgroup per (list entry,
 // head) in list order, so the hardware dispatcher hands out the heaviest tiles first and the
 // light ones fill the tail (longest-processing-time-first list scheduling).
+#include <vector>
+
 #include "va_device.h"
 #include "va_internal.h"
 
 namespace va {
 
 constexpr int SCHED_THREADS = 1024;
-constexpr int SCHED_BINS = 4096;  // costs above SCHED_BINS-1 share the top bin
 
 SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows) {
     SchedLayout lay;
@@ -45,18 +46,9 @@ __device__ int block_exclusive_scan(int v, int* buf, int* total) {
     return incl - v;
 }
 
-__device__ __forceinline__ int tile_cost(int L, int t, int R, int U, int mode) {
-    int span;
-    if (mode == COST_FULL) span = L;
-    else if (mode == COST_CAUSAL_QUERY) span = min(L, (t + 1) * R);
-    else span = L - t * R;
-    int c = (span + U - 1) / U;
-    return min(c, SCHED_BINS - 1);
-}
-
 __global__ void __launch_bounds__(SCHED_THREADS)
-sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int32_t* __restrict__ hdr,
-             int32_t* __restrict__ tile_off, WorkItem* __restrict__ items) {
+sched_kernel(const int32_t* __restrict__ cu, int B, int T, int max_items, int R, int U, int mode,
+             int32_t* __restrict__ hdr, int32_t* __restrict__ tile_off, WorkItem* __restrict__ items) {
     __shared__ int scan_buf[SCHED_THREADS];
     __shared__ int bins[SCHED_BINS];
     __shared__ int longest;
@@ -70,7 +62,9 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
         int s = base + t;
         int n = 0;
         if (s < B) {
-            const int len = cu[s + 1] - cu[s];
+            int begin, end;
+            sched_sample_rows(cu[s], cu[s + 1], T, begin, end);
+            const int len = end - begin;
             n = (len + R - 1) / R;
             if (len >= kXcdChunkMinLen) longest = len;  // (any such length will do: only the threshold matters)
         }
@@ -79,7 +73,9 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
         if (s < B) tile_off[s] = carry + ex;
         carry += total;
     }
-    const int n_items = carry;
+    // (a well-formed batch has at most max_items tiles; one that is not loses the surplus instead of
+    // writing past the list)
+    const int n_items = min(carry, max_items);
     if (t == 0) {
         tile_off[B] = n_items;
         hdr[0] = n_items;
@@ -95,8 +91,9 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
             int mid = (lo + hi) >> 1;
             if (tile_off[mid] <= idx) lo = mid; else hi = mid;
         }
-        int L = cu[lo + 1] - cu[lo];
-        atomicAdd(&bins[tile_cost(L, idx - tile_off[lo], R, U, mode)], 1);
+        int begin, end;
+        sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
+        atomicAdd(&bins[sched_tile_cost(end - begin, idx - tile_off[lo], R, U, mode)], 1);
     }
     __syncthreads();
 
@@ -125,20 +122,46 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int R, int U, int mode, int3
             int mid = (lo + hi) >> 1;
             if (tile_off[mid] <= idx) lo = mid; else hi = mid;
         }
-        int begin = cu[lo], end = cu[lo + 1];
+        int begin, end;
+        sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
         int tile = idx - tile_off[lo];
-        int pos = atomicAdd(&bins[tile_cost(end - begin, tile, R, U, mode)], 1);
+        int pos = atomicAdd(&bins[sched_tile_cost(end - begin, tile, R, U, mode)], 1);
         items[pos] = make_int4(begin + tile * R, begin, end, tile);
     }
 }
 
-hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int tile_rows, int partner_rows,
-                            CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream) {
+hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows,
+                            int partner_rows, CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream) {
     char* base = (char*)ws;
-    hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs,
-                       tile_rows, partner_rows, (int)mode, (int32_t*)base,
+    hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs, total_tokens,
+                       (int)lay.max_items, tile_rows, partner_rows, (int)mode, (int32_t*)base,
                        (int32_t*)(base + lay.tile_off_ofs), (WorkItem*)(base + lay.items_ofs));
     return hipGetLastError();
+}
+
+int64_t schedule_on_host(const int32_t* cu, int B, int T, int R, int U, CostMode mode, int64_t max_items,
+                         WorkItem* items) {
+    // counting sort by cost class, heaviest first; inside a class the tiles keep their (sample, tile) order
+    std::vector<int64_t> start(SCHED_BINS + 1, 0);
+    int64_t n = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        int64_t seen = 0;
+        for (int s = 0; s < B && seen < max_items; ++s) {
+            int begin, end;
+            sched_sample_rows(cu[s], cu[s + 1], T, begin, end);
+            const int L = end - begin;
+            for (int t = 0; t * (int64_t)R < L && seen < max_items; ++t, ++seen) {
+                const int c = sched_tile_cost(L, t, R, U, (int)mode);
+                if (pass == 0) ++start[SCHED_BINS - 1 - c + 1];
+                else items[start[SCHED_BINS - 1 - c]++] = make_int4(begin + t * R, begin, end, t);
+            }
+        }
+        if (pass == 0) {
+            n = seen;
+            for (int i = 0; i < SCHED_BINS; ++i) start[i + 1] += start[i];
+        }
+    }
+    return n;
 }
 
 // One workgroup walks cu_seqlens; every thread notes what it sees wrong, the block ORs the notes.

@@ -35,9 +35,14 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_params_struct_matches_header():
     from paper_2605_08962_amd import binding
-    assert ctypes.sizeof(binding.Params) == 32
+    assert ctypes.sizeof(binding.Params) == 36
     assert [f[0] for f in binding.Params._fields_] == [
-        "total_tokens", "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "causal", "softmax_scale", "kv_splits"]
+        "total_tokens", "num_seqs", "num_q_heads", "num_kv_heads", "head_dim", "causal", "softmax_scale", "max_seqlen",
+        "kv_splits"]
+    # the header's struct, member by member, in the same order
+    text = open(os.path.join(ROOT, "include", "varlen_attn.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", text[text.index("typedef struct {"):text.index("} varlen_attn_params;")], flags=re.S)
+    assert re.findall(r"(?:int32_t|float)\s+(\w+);", body) == [f[0] for f in binding.Params._fields_]
 
 
 def test_status_strings(lib):
@@ -65,6 +70,8 @@ def test_host_side_validation_needs_no_gpu(lib):
     for bad in (-1, 9):
         p = mk(8, 1, 2, 2, 64, 0, 0.125); p.kv_splits = bad
         assert _call_fwd(lib, p) == 2
+    p = mk(8, 1, 2, 2, 64, 0, 0.125); p.max_seqlen = -1
+    assert _call_fwd(lib, p) == 2
     for d in (0, 32, 48, 72, 256):
         assert _call_fwd(lib, mk(8, 1, 2, 2, d, 0, 0.125)) == 3
     for s in (float("nan"), float("inf"), -0.5):
@@ -115,6 +122,65 @@ def test_workspace_and_work_list_bounds():
         assert fw >= 64 + 4 * (B + 1) + 16 * binding.max_work_items(p, 0) and fw % 256 == 0
         assert bw >= 4 * T * 8 + fw
     assert binding.fwd_workspace_bytes(binding.make_params(8, 1, 2, 2, 72, 0, 0.1)) == 0
+
+
+def _host_schedule(binding, lib, cu, T, causal, which):
+    cu = np.ascontiguousarray(cu, dtype=np.int32)
+    p = binding.make_params(T, cu.size - 1, 1, 1, 64, causal, 0.125)
+    cap = binding.max_work_items(p, which)
+    items = np.full((cap + 1, 4), -7, dtype=np.int32)          # one guard row behind the list
+    lib.varlen_attn_schedule_host.restype = ctypes.c_int64
+    lib.varlen_attn_schedule_host.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_int64]
+    n = lib.varlen_attn_schedule_host(ctypes.byref(p), which, cu.ctypes.data, items.ctypes.data, cap)
+    assert 0 <= n <= cap and (items[n:] == -7).all()
+    return items[:n]
+
+
+def test_host_schedule_matches_the_oracle(lib):
+    """The work list arithmetic the device scheduler shares with the host (sample clamp, tile cost, counting
+    sort by cost) against oracle/schedule.py: same tiles, each once, heaviest first."""
+    from oracle import schedule
+    from paper_2605_08962_amd import binding
+    rng = np.random.default_rng(5)
+    cases = [np.array([16, 37, 64, 129]), np.array([0, 300, 0, 0, 129, 1, 0, 128, 127, 0]), np.array([5000]),
+             W.make(3, lengths_only=True).lengths, W.make(4, lengths_only=True).lengths, rng.integers(0, 200, size=700)]
+    for lengths in cases:
+        cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+        for causal in (0, 1):
+            for which, mode in ((0, "causal_query" if causal else "full"), (1, "causal_key" if causal else "full"),
+                                (2, "causal_query" if causal else "full")):
+                got = _host_schedule(binding, lib, cu, int(cu[-1]), causal, which)
+                want = schedule.work_items(cu, 128, 64, mode)
+                cost_of = {it[:4]: it[4] for it in want}
+                keys = [tuple(int(x) for x in row) for row in got]
+                assert len(keys) == len(want) and set(keys) == set(cost_of)
+                assert np.all(np.diff([cost_of[k_] for k_ in keys]) <= 0)
+
+
+def test_schedule_of_a_malformed_batch_stays_inside_the_tensors(lib):
+    """cu_seqlens lives on the device and is not validated.  The scheduler clamps each sample into
+    [0, T) and the list to the room the workspace has, so that a malformed array cannot make the
+    attention kernels address memory outside the tensors (checked here on the host-side twin of the
+    device arithmetic; no GPU is given a malformed batch)."""
+    from paper_2605_08962_amd import binding
+    T = 1000
+    bad = [[0, 400, 2000], [0, -5, 1000], [0, 700, 300, 1000], [0, 1000, 0, 1000, 0, 1000, 0, 1000], [5, 9, 1 << 30],
+           [0, -(1 << 31), (1 << 31) - 1], [0, 1000, 1000, 1000]]
+    for cu in bad:
+        for causal in (0, 1):
+            for which in (0, 1, 2):
+                items = _host_schedule(binding, lib, np.array(cu, dtype=np.int64).astype(np.int32), T, causal, which)
+                first, begin, end, tile = items.T
+                assert (0 <= begin).all() and (begin <= first).all() and (first < end).all() and (end <= T).all()
+                assert (first == begin + 128 * tile).all()
+    # bad arguments: no list
+    p = binding.make_params(T, 2, 1, 1, 64, 0, 0.125)
+    buf = np.zeros((64, 4), dtype=np.int32)
+    cu = np.array([0, 500, 1000], dtype=np.int32)
+    assert lib.varlen_attn_schedule_host(ctypes.byref(p), 3, cu.ctypes.data, buf.ctypes.data, 64) == -1
+    assert lib.varlen_attn_schedule_host(ctypes.byref(p), 0, cu.ctypes.data, buf.ctypes.data, 2) == -1
+    assert lib.varlen_attn_schedule_host(ctypes.byref(p), 0, None, buf.ctypes.data, 64) == -1
 
 
 def test_workload_recipes():
