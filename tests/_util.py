@@ -61,3 +61,29 @@ def assert_close(name, got, ref, max_abs=MAX_ABS, rel_rms=REL_RMS, allow_output_
     a, r = errors(got, ref)
     assert a <= max_abs and r <= rel_rms, f"{name}: max_abs={a:.3e} (<= {max_abs}) rel_rms={r:.3e} (<= {rel_rms})"
     return a, r
+
+
+def assert_gradients_close(label, got, q, k, v, dout, cu, causal, scale, o_saved, allow_output_rounding=False,
+                           rel_rms=REL_RMS, max_abs=MAX_ABS):
+    """Gradient parity at the stated bounds.  got = (dQ, dK, dV) float64 from the GPU; q, k, v, dout float32
+    arrays of the same slice; o_saved = the forward output the GPU backward was given (what a training step
+    stores: bf16), as float64.
+
+    The backward interface takes O as stored, so Delta = <dO, O> inherits O's bf16 rounding whatever the
+    kernels do.  The reference is therefore the exact (fp64) gradient arithmetic on the inputs the call
+    received, the stored O included: oracle.bwd(..., o_saved=...), held to max abs 1e-2 / relative RMS 5e-3.
+    The distance between that and the oracle on its own fp64 O, printed beside it, is the cost of the
+    interface, not of the kernels.  Returns [(max_abs, rel_rms)] per tensor against the stored-O reference."""
+    import oracle
+    ref = oracle.bwd(q, k, v, dout, cu, causal, scale, o_saved=o_saved)
+    own = oracle.bwd(q, k, v, dout, cu, causal, scale)
+    out = []
+    for name, g_, r_, o_ in zip(("dQ", "dK", "dV"), got, ref, own):
+        a, r = assert_close(f"{name}[{label}]", g_, r_, max_abs=max_abs, rel_rms=rel_rms,
+                            allow_output_rounding=allow_output_rounding)
+        iface = float(np.abs(r_ - o_).max()) if r_.size else 0.0
+        vs_own = float(np.abs(g_ - o_).max()) if r_.size else 0.0
+        print(f"   {name}[{label}]: max_abs={a:.2e} rel_rms={r:.2e} | stored-O vs own-O oracle {iface:.2e}, "
+              f"GPU vs own-O oracle {vs_own:.2e}", flush=True)
+        out.append((a, r))
+    return out
