@@ -59,7 +59,9 @@ enum {
     VA_ERR_BAD_SCALE = 5,           /* softmax_scale is NaN, infinite or negative */
     VA_ERR_HIP = 6,                 /* a HIP call failed; see varlen_attn_last_hip_error() */
     VA_ERR_MISALIGNED = 7,          /* a tensor or workspace pointer is not 16-byte aligned */
-    VA_ERR_BAD_CU_SEQLENS = 8       /* varlen_attn_check_cu_seqlens only: the device array breaks the precondition */
+    VA_ERR_BAD_CU_SEQLENS = 8,      /* varlen_attn_check_cu_seqlens only: the device array breaks the precondition */
+    VA_ERR_SCRATCH_LIMIT = 9        /* varlen_attn_fwd_static_scratch only: the call needs more scratch than
+                                       VA_STATIC_SCRATCH_BYTES */
 };
 
 typedef struct {
@@ -100,6 +102,28 @@ int varlen_attn_fwd(const varlen_attn_params *p,
                     const int32_t *cu_seqlens,
                     void *o, float *lse,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The forward for callers that can neither allocate device memory nor hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as varlen_attn_fwd, bit for bit, minus the workspace: the scratch the call needs (the
+ * scheduler's work list and, when the keys of a query tile are split, the fp32 partial results) lives in
+ * an array of VA_STATIC_SCRATCH_BYTES that is part of the library's device code.  Every GPU the library
+ * runs on holds its own copy of it from the first call there until the process ends.  The call allocates
+ * nothing and calls no allocating routine; the first call on a device looks the array's address up
+ * (hipGetSymbolAddress) and keeps it.
+ * Limit: a call whose varlen_attn_fwd_workspace_bytes(p) exceeds VA_STATIC_SCRATCH_BYTES returns
+ * VA_ERR_SCRATCH_LIMIT with nothing launched (kv_splits = 1 shrinks the need to the work list: 16 bytes per
+ * 128 tokens and 20 per sample).
+ * All calls on one GPU share that GPU's array, whatever their stream or thread: calls that overlap in time
+ * on one GPU race on it and must be ordered by the caller (one stream, or events).  Nothing in it has to
+ * start at zero: every call rewrites what it reads.
+ */
+enum { VA_STATIC_SCRATCH_BYTES = 32 << 20 };
+int varlen_attn_fwd_static_scratch(const varlen_attn_params *p,
+                                   const void *q, const void *k, const void *v,
+                                   const int32_t *cu_seqlens,
+                                   void *o, float *lse, void *hip_stream);
 
 /*
  * Backward: writes dq, dk, dv from dout and the forward's saved o and lse (P is recomputed from

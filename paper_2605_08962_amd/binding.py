@@ -49,6 +49,8 @@ def load():
     lib.varlen_attn_max_work_items.restype = ctypes.c_int64
     lib.varlen_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.varlen_attn_fwd.restype = ctypes.c_int
+    lib.varlen_attn_fwd_static_scratch.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
+    lib.varlen_attn_fwd_static_scratch.restype = ctypes.c_int
     lib.varlen_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.varlen_attn_bwd.restype = ctypes.c_int
     lib.varlen_attn_merge.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp]
@@ -140,6 +142,30 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, causal, softmax_scale, out=None, lse=No
     _check(lib.varlen_attn_fwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                cu_seqlens.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                workspace.data_ptr(), workspace.numel(), _stream_handle(stream)))
+    return out, lse
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+VA_ERR_SCRATCH_LIMIT = 9
+
+
+def varlen_attn_fwd_static_scratch(q, k, v, cu_seqlens, causal, softmax_scale, out, lse, stream=None, kv_splits=0,
+                                   max_seqlen=0):
+    """varlen_attn_fwd without a workspace: the scratch lives in a static device array of the library.  The
+    caller passes the outputs; nothing is allocated here or in the library."""
+    lib = load()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (out, "out")):
+        _require(t, torch.bfloat16, n)
+    _require(lse, torch.float32, "lse")
+    _require(cu_seqlens, torch.int32, "cu_seqlens")
+    if k.shape != v.shape or k.shape[0] != q.shape[0] or k.shape[2] != q.shape[2] or out.shape != q.shape:
+        raise ValueError("k and v must be [T, Hkv, D] matching q's T and D; out must match q")
+    if tuple(lse.shape) != (q.shape[1], q.shape[0]):
+        raise ValueError("lse must be [Hq, T]")
+    p = _params_of(q, k, cu_seqlens, causal, softmax_scale, kv_splits, max_seqlen)
+    _check(lib.varlen_attn_fwd_static_scratch(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                              cu_seqlens.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                              _stream_handle(stream)))
     return out, lse
 
 

@@ -8,6 +8,10 @@
 #include "../../include/varlen_attn.h"
 #include "va_internal.h"
 
+// Scratch of varlen_attn_fwd_static_scratch: device memory that belongs to the library's code object, one
+// copy per GPU.  In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[VA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -220,6 +224,44 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     return VA_OK;
 }
 
+namespace {
+// Address of `scratch` on the current device, looked up once per device (with that device current).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_ptr(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return VA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return VA_OK;
+}
+}  // namespace
+
+int varlen_attn_fwd_static_scratch(const varlen_attn_params* p, const void* q, const void* k, const void* v,
+                                   const int32_t* cu_seqlens, void* o, float* lse, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != VA_OK) return rc;
+    if (p->total_tokens == 0 || p->num_seqs == 0) return VA_OK;
+    if (fwd_layout(p).end > (size_t)VA_STATIC_SCRATCH_BYTES) return VA_ERR_SCRATCH_LIMIT;
+    rc = check_device();
+    if (rc != VA_OK) return rc;
+    void* ptr = nullptr;
+    rc = static_scratch_ptr(&ptr);
+    if (rc != VA_OK) return rc;
+    return varlen_attn_fwd(p, q, k, v, cu_seqlens, o, lse, ptr, (size_t)VA_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 int varlen_attn_merge(const varlen_attn_params* p, int32_t num_parts, const void* o_parts, const float* lse_parts,
                       void* o, float* lse, void* hip_stream) {
     int rc = check_params(p);
@@ -335,6 +377,7 @@ const char* varlen_attn_status_string(int status) {
         case VA_ERR_HIP: return "a HIP call failed";
         case VA_ERR_MISALIGNED: return "a tensor or workspace pointer is not 16-byte aligned";
         case VA_ERR_BAD_CU_SEQLENS: return "cu_seqlens must start at 0, never decrease and end at total_tokens";
+        case VA_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the library's static array holds (VA_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }

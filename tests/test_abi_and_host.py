@@ -47,8 +47,8 @@ def test_params_struct_matches_header():
 
 def test_status_strings(lib):
     from paper_2605_08962_amd import binding
-    seen = {binding.status_string(i) for i in range(9)}
-    assert len(seen) == 9 and binding.status_string(0) == "ok"
+    seen = {binding.status_string(i) for i in range(10)}
+    assert len(seen) == 10 and binding.status_string(0) == "ok"
     assert binding.status_string(99) == "unknown status"
 
 
