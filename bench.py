@@ -25,20 +25,86 @@ sys.path.insert(0, ROOT)
 
 METRIC = "varlen attention useful TFLOP/s fwd/bwd on 1 MI355X; % of bf16 MFMA peak"
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), or None.
-# Read off profiles/bench_*_fwd_bwd.md: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per dispatch,
-# the factors being what the same counters read for a 1 GiB device copy in the same run.
-MEASURED_TRAFFIC_BYTES = {
-    ("llm_causal_gqa_d128", "dkdv"): int((2.0 * 3.51e+06 + 1.312e+05) * 1024),
-    ("llm_causal_gqa_d128", "dq"): int((2.0 * 1.001e+06 + 2.712e+05) * 1024),
-    ("llm_causal_gqa_d128", "fwd"): int((2.0 * 7.145e+05 + 2.668e+05) * 1024),
-    ("long_short_mix_d80", "dkdv"): int((2.0 * 5.14e+06 + 8.147e+05) * 1024),
-    ("long_short_mix_d80", "dq"): int((2.0 * 5.531e+06 + 3.923e+05) * 1024),
-    ("long_short_mix_d80", "fwd"): int((2.0 * 4.851e+06 + 3.833e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dkdv"): int((2.0 * 9.467e+05 + 7.157e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "dq"): int((2.0 * 1.101e+06 + 3.806e+05) * 1024),
-    ("vit_dynamic_resolution_d64_fwd_bwd", "fwd"): int((2.0 * 6.169e+05 + 3.694e+05) * 1024),
-}
+CSRC = os.path.join(ROOT, "paper_2605_08962_amd", "csrc")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.json")
+KERNEL_SYMBOL = {"fwd": "fwd_kernel", "dkdv": "dkdv_kernel", "dq": "dq_kernel"}
+
+
+def kernel_source_hash():
+    """sha256 over the kernel sources (names and contents): ties a counter reading to the code it measured."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _instance(kernel, head_dim, causal):
+    return f"{KERNEL_SYMBOL[kernel]}<{head_dim}, {'true' if causal else 'false'}>"
+
+
+def measured_traffic(kernel, head_dim, causal):
+    """HBM bytes per launch of a kernel instance from the rocprofv3 --pmc readings that
+    `bench.py --record-traffic` stored, or None when there is none for the kernel sources as they are now
+    (a reading taken on other code says nothing about this code)."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_source_sha16") != kernel_source_hash():
+        return None
+    e = rec.get("kernels", {}).get(_instance(kernel, head_dim, causal))
+    return None if e is None else int(e["bytes"])
+
+
+def record_traffic(paths):
+    """Reads the counter_collection.csv files of rocprofv3 --pmc runs of `bench.py --calibrate-copy`
+    (FETCH_SIZE in one run, WRITE_SIZE in another), scales each counter by what it read for the 1 GiB
+    device copy of the same run, and stores HBM bytes per launch per kernel instance in profiles/, together
+    with the hash of the kernel sources they were measured on.  The kernel instances name the workload:
+    <64, false> is the ViT batch (configs 2 and 5), <80, false> the long/short mix, <128, true> the LLM batch."""
+    import csv
+    import glob
+    val = {}    # (counter, kernel name) -> [sum of readings (KiB), dispatch ids]
+    for path in paths:
+        files = glob.glob(os.path.join(path, "**", "*counter_collection.csv"), recursive=True) if os.path.isdir(path) else [path]
+        for f in files:
+            for row in csv.DictReader(open(f)):
+                acc = val.setdefault((row["Counter_Name"], row["Kernel_Name"]), [0.0, set()])
+                acc[0] += float(row["Counter_Value"])
+                acc[1].add((f, row["Dispatch_Id"]))
+    factor = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        copies = [v / len(ids) for (c, name), (v, ids) in val.items() if c == counter and "copyBuffer" in name]
+        if not copies:
+            raise SystemExit(f"no device-copy kernel with a {counter} reading: profile `bench.py --calibrate-copy`")
+        factor[counter] = float(1 << 30) / (max(copies) * 1024.0)   # true bytes per counted byte
+    kernels = {}
+    for (counter, name), (v, ids) in val.items():
+        for sym in KERNEL_SYMBOL.values():
+            at = name.find("va::" + sym + "<")
+            if at < 0 or counter not in factor:
+                continue
+            inst = name[at + 4:name.index(">", at) + 1]
+            e = kernels.setdefault(inst, {})
+            e[counter.lower() + "_kib_per_dispatch"] = round(v / len(ids), 1)
+            e["dispatches"] = len(ids)
+    for inst, e in kernels.items():
+        if "fetch_size_kib_per_dispatch" in e and "write_size_kib_per_dispatch" in e:
+            e["bytes"] = int(1024.0 * (e["fetch_size_kib_per_dispatch"] * factor["FETCH_SIZE"] +
+                                       e["write_size_kib_per_dispatch"] * factor["WRITE_SIZE"]))
+    out = {"kernel_source_sha16": kernel_source_hash(),
+           "method": "rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE (KiB per dispatch, mean over the run's dispatches), "
+                     "each times the factor that makes the same counter read 1 GiB for the 1 GiB device copy of the "
+                     "same run",
+           "calibration_true_bytes_per_counted_byte": {k: round(v, 4) for k, v in factor.items()},
+           "kernels": {k: kernels[k] for k in sorted(kernels) if "bytes" in kernels[k]}}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out, indent=1))
 
 
 def cpu_baseline(w, budget_flops=8e11):
@@ -320,6 +386,78 @@ def small_launch(args, torch, binding, W):
               f"{nbytes / ms / 1e6 / 8000:.3f} |", flush=True)
 
 
+def measure(args, torch, binding, to_gpu_bf16, w, with_bwd, steps, warmup, settle_s):
+    """W warm-up steps, then further untimed steps until settle_s seconds of continuous load have passed (the
+    chip lowers its clock under matrix-core load; a timed region that starts cold flatters it), then exactly
+    `steps` timed steps between two synchronisations.  Per-kernel durations from HIP events the library records
+    around each launch on the caller's stream."""
+    q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
+    cu = torch.from_numpy(w.cu_seqlens).cuda()
+    T = w.total_tokens
+    p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale)
+    o = torch.empty_like(q)
+    lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
+    ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f)
+        if with_bwd:
+            binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
+                                    workspace=ws_b)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < settle_s:
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+    clocks = torch.zeros(6, dtype=torch.int64, device="cuda")
+    binding.profile_clock_probe(clocks)
+    binding.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.profile_enable(False)
+    binding.profile_clock_probe(None)
+    prof = binding.profile_read()
+    ck = clocks.cpu().tolist()
+
+    fwd_flops = w.fwd_flops()
+    step_flops = fwd_flops * (3.5 if with_bwd else 1.0)
+    ms = dt * 1e3 / steps
+    value = step_flops / (ms * 1e-3) / 1e12
+    # algorithmic flops per launch: forward = F; dK/dV kernel = S, dP, dV, dK = 4 of the backward's 5
+    # GEMMs = 2.0 F; dQ kernel = the dQ GEMM = 0.5 F (its recomputation of S and dP is not counted).
+    algo = {"fwd": fwd_flops, "dkdv": 2.0 * fwd_flops, "dq": 0.5 * fwd_flops}
+    kern = {n: (prof[n][0] / prof[n][1]) for n in algo if prof[n][1] > 0}
+    dom = max(kern, key=lambda n: kern[n] * prof[n][1])
+    achieved = algo[dom] / (kern[dom] * 1e-3) / 1e12
+    res = {
+        "passes": "fwd+bwd" if with_bwd else "fwd", "ms_per_step": round(ms, 4), "tflops": round(value, 2),
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "kernels_ms": {n: round(prof[n][0] / max(prof[n][1], 1), 4) for n in prof if prof[n][1] > 0},
+        "fwd_tflops": round(fwd_flops / (kern["fwd"] * 1e-3) / 1e12, 2),
+        "roofline": {"kernel": _instance(dom, w.head_dim, w.causal), "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": measured_traffic(dom, w.head_dim, w.causal)},
+        # average shader clock each compute kernel ran at (cycle counter over the 100 MHz constant clock)
+        "shader_clock_ghz": {n: round(0.1 * ck[2 * i + 1] / ck[2 * i], 3)
+                             for i, n in enumerate(("fwd", "dkdv", "dq")) if ck[2 * i] > 0},
+    }
+    if with_bwd:
+        bwd_ms = sum(kern[n] for n in ("dkdv", "dq"))
+        res["bwd_tflops"] = round(2.5 * fwd_flops / (bwd_ms * 1e-3) / 1e12, 2)
+    del q, k, v, do, o, lse, ws_f, ws_b, dq, dk, dv
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -351,10 +489,22 @@ def main():
                     help="equal-length samples of 64..2048 tokens: HBM GB/s at the minimum bytes and useful "
                          "TFLOP/s, forward and backward; prints a markdown table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="leave the per-config list (configs 2, 3, 4) out of the JSON line")
+    ap.add_argument("--settle-s", type=float, default=1.0,
+                    help="seconds of untimed steps after the warm-up, so that the timed steps run at the clock "
+                         "the chip settles at under sustained load (default 1.0)")
+    ap.add_argument("--record-traffic", nargs="+", metavar="DIR",
+                    help="no GPU work: read rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE output directories of "
+                         "`bench.py --calibrate-copy` runs and store HBM bytes per launch per kernel in "
+                         "profiles/hbm_traffic_per_kernel.json, which later runs report as roofline.traffic")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, as the known-size reference that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
+    if args.record_traffic:
+        record_traffic(args.record_traffic)
+        return
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU only (no sharding, no collectives); "
                          "use --gpus 1\n")
@@ -383,24 +533,6 @@ def main():
         short_regime(args, torch, binding)
         return
 
-    with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5
-    w = W.make(args.config, with_dout=True)
-    q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
-    cu = torch.from_numpy(w.cu_seqlens).cuda()
-    T = w.total_tokens
-    p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale)
-    o = torch.empty_like(q)
-    lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
-    ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
-    ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-
-    def step():
-        binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f)
-        if with_bwd:
-            binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
-                                    workspace=ws_b)
-
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -408,53 +540,37 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    clocks = torch.zeros(6, dtype=torch.int64, device="cuda")
-    binding.profile_clock_probe(clocks)
-    binding.profile_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    binding.profile_enable(False)
-    binding.profile_clock_probe(None)
-    prof = binding.profile_read()
-    ck = clocks.cpu().tolist()
 
-    fwd_flops = w.fwd_flops()
-    step_flops = fwd_flops * (3.5 if with_bwd else 1.0)
-    ms = dt * 1e3 / args.steps
-    value = step_flops / (ms * 1e-3) / 1e12
-
-    # algorithmic flops per launch: forward = F; dK/dV kernel = S, dP, dV, dK = 4 of the backward's 5
-    # GEMMs = 2.0 F; dQ kernel = the dQ GEMM = 0.5 F (its recomputation of S and dP is not counted).
-    algo = {"fwd": fwd_flops, "dkdv": 2.0 * fwd_flops, "dq": 0.5 * fwd_flops}
-    kern = {n: (prof[n][0] / prof[n][1]) for n in algo if prof[n][1] > 0}
-    dom = max(kern, key=lambda n: kern[n] * prof[n][1])
-    achieved = algo[dom] / (kern[dom] * 1e-3) / 1e12
+    with_bwd = (args.passes == "fwd+bwd") if args.passes else args.config == 5
+    w = W.make(args.config, with_dout=True)
+    head = measure(args, torch, binding, to_gpu_bf16, w, with_bwd, args.steps, args.warmup, args.settle_s)
     out = {
-        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC, "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "num_seqs": w.num_seqs, "total_tokens": T,
+        "config": {"workload": w.name, "num_seqs": w.num_seqs, "total_tokens": w.total_tokens,
                    "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
-                   "causal": w.causal, "passes": "fwd+bwd" if with_bwd else "fwd", "seed": w.seed},
-        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "kernels_ms": {n: round(prof[n][0] / max(prof[n][1], 1), 4) for n in prof if prof[n][1] > 0},
-        "fwd_tflops": round(fwd_flops / (kern["fwd"] * 1e-3) / 1e12, 2),
-        "roofline": {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
+                   "causal": w.causal, "passes": head["passes"], "seed": w.seed},
+        "pct_of_bf16_mfma_peak": head["pct_of_bf16_mfma_peak"],
+        "settle_s": args.settle_s,
+        "kernels_ms": head["kernels_ms"], "fwd_tflops": head["fwd_tflops"],
+        "roofline": head["roofline"], "shader_clock_ghz": head["shader_clock_ghz"],
     }
-    # average shader clock each compute kernel ran at (cycle counter over the 100 MHz constant clock)
-    out["shader_clock_ghz"] = {n: round(0.1 * ck[2 * i + 1] / ck[2 * i], 3)
-                               for i, n in enumerate(("fwd", "dkdv", "dq")) if ck[2 * i] > 0}
-    if with_bwd:
-        bwd_ms = sum(kern[n] for n in ("dkdv", "dq"))
-        out["bwd_tflops"] = round(2.5 * fwd_flops / (bwd_ms * 1e-3) / 1e12, 2)
+    if "bwd_tflops" in head:
+        out["bwd_tflops"] = head["bwd_tflops"]
+    # the other long-sequence configurations, each as a forward-only step and as a forward+backward step
+    if args.config == 5 and args.passes is None and not args.headline_only:
+        out["configs"] = []
+        for cfg in (2, 3, 4):
+            wc = W.make(cfg, with_dout=True)
+            for wb in (False, True):
+                if cfg == 2 and wb:
+                    continue        # config 2 forward+backward IS the headline step (config 5)
+                r = measure(args, torch, binding, to_gpu_bf16, wc, wb, args.steps, args.warmup, min(args.settle_s, 0.5))
+                r.update({"workload": wc.name, "head_dim": wc.head_dim, "causal": wc.causal,
+                          "total_tokens": wc.total_tokens, "num_seqs": wc.num_seqs})
+                out["configs"].append(r)
+            del wc
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
