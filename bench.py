@@ -15,6 +15,7 @@ sample of the same batch.
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -68,6 +69,7 @@ def record_traffic(paths):
     import csv
     import glob
     val = {}    # (counter, kernel name) -> [sum of readings (KiB), dispatch ids]
+    largest_copy = {}   # counter -> largest single reading of a device-copy dispatch: the 1 GiB one
     for path in paths:
         files = glob.glob(os.path.join(path, "**", "*counter_collection.csv"), recursive=True) if os.path.isdir(path) else [path]
         for f in files:
@@ -75,19 +77,29 @@ def record_traffic(paths):
                 acc = val.setdefault((row["Counter_Name"], row["Kernel_Name"]), [0.0, set()])
                 acc[0] += float(row["Counter_Value"])
                 acc[1].add((f, row["Dispatch_Id"]))
+                if "copyBuffer" in row["Kernel_Name"]:
+                    c = row["Counter_Name"]
+                    largest_copy[c] = max(largest_copy.get(c, 0.0), float(row["Counter_Value"]))
     factor = {}
     for counter in ("FETCH_SIZE", "WRITE_SIZE"):
-        copies = [v / len(ids) for (c, name), (v, ids) in val.items() if c == counter and "copyBuffer" in name]
-        if not copies:
+        if largest_copy.get(counter, 0.0) < 1024.0:
             raise SystemExit(f"no device-copy kernel with a {counter} reading: profile `bench.py --calibrate-copy`")
-        factor[counter] = float(1 << 30) / (max(copies) * 1024.0)   # true bytes per counted byte
+        factor[counter] = float(1 << 30) / (largest_copy[counter] * 1024.0)   # true bytes per counted byte
     kernels = {}
     for (counter, name), (v, ids) in val.items():
         for sym in KERNEL_SYMBOL.values():
-            at = name.find("va::" + sym + "<")
-            if at < 0 or counter not in factor:
+            # demangled "va::fwd_kernel<64, false>(...)", or, where the profiler's demangler gave up, the
+            # mangled "_ZN2va11dkdv_kernelILi64ELb0EEEv..."
+            m = re.search(r"va::%s<(\d+), (true|false)>" % sym, name)
+            if m:
+                inst = f"{sym}<{m.group(1)}, {m.group(2)}>"
+            else:
+                m = re.search(r"\d+%sILi(\d+)ELb([01])E" % sym, name)
+                if not m:
+                    continue
+                inst = f"{sym}<{m.group(1)}, {'true' if m.group(2) == '1' else 'false'}>"
+            if counter not in factor:
                 continue
-            inst = name[at + 4:name.index(">", at) + 1]
             e = kernels.setdefault(inst, {})
             e[counter.lower() + "_kib_per_dispatch"] = round(v / len(ids), 1)
             e["dispatches"] = len(ids)
