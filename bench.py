@@ -159,7 +159,9 @@ def report(args, torch, binding, W, to_gpu_bf16):
         q, k, v, do = (to_gpu_bf16(getattr(w, n)) for n in ("q", "k", "v", "dout"))
         cu = torch.from_numpy(w.cu_seqlens).cuda()
         T = w.total_tokens
-        p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale)
+        longest = int(w.lengths.max())      # the max_seqlen a caller of a varlen interface passes along
+        p = binding.make_params(T, w.num_seqs, w.num_q_heads, w.num_kv_heads, w.head_dim, w.causal, w.scale,
+                                max_seqlen=longest)
         o = torch.empty_like(q)
         lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
         ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
@@ -167,7 +169,7 @@ def report(args, torch, binding, W, to_gpu_bf16):
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
 
         def fwd():
-            binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f)
+            binding.varlen_attn_fwd(q, k, v, cu, w.causal, w.scale, out=o, lse=lse, workspace=ws_f, max_seqlen=longest)
 
         def bwd():
             binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, w.causal, w.scale, dq=dq, dk=dk, dv=dv,
@@ -323,13 +325,15 @@ def short_regime(args, torch, binding):
             q, k, v, do = (torch.randn((T, H, D), device="cuda", dtype=torch.bfloat16, generator=g) for _ in range(4))
             cu = torch.arange(0, T + 1, L, dtype=torch.int32, device="cuda")
             scale = D ** -0.5
-            p = binding.make_params(T, B, H, H, D, False, scale)
+            p = binding.make_params(T, B, H, H, D, False, scale, max_seqlen=L)
             ws_f = torch.empty(binding.fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
             ws_b = torch.empty(binding.bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
             o = torch.empty_like(q)
             lse = torch.empty((H, T), dtype=torch.float32, device="cuda")
             dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-            fns = (("fwd", lambda: binding.varlen_attn_fwd(q, k, v, cu, False, scale, out=o, lse=lse, workspace=ws_f),
+            # (a caller of a varlen interface knows its longest sample; the hint selects the lean forward)
+            fns = (("fwd", lambda: binding.varlen_attn_fwd(q, k, v, cu, False, scale, out=o, lse=lse, workspace=ws_f,
+                                                           max_seqlen=L),
                     2 * D * T * 4 * H + 4 * T * H, 1.0),
                    ("bwd", lambda: binding.varlen_attn_bwd(do, q, k, v, o, lse, cu, False, scale, dq=dq, dk=dk, dv=dv,
                                                            workspace=ws_b),

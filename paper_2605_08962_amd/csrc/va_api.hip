@@ -96,6 +96,8 @@ int check_device() {
 // launch cannot fill the chip: fewer workgroups than the 256 CUs can hold at once (3 per CU at
 // head_dim <= 80, else 2), and samples long enough that every chunk still gets two key tiles (judged by
 // the caller's max_seqlen if it gave one, else by the average sample).
+bool short_batch(const varlen_attn_params* p) { return p->max_seqlen > 0 && p->max_seqlen <= va::kShortBatchMaxSeqlen; }
+
 int fwd_kv_splits(const varlen_attn_params* p) {
     if (p->kv_splits >= 1) return p->kv_splits;
     const int64_t wgs = ((int64_t)p->total_tokens / va::FWD_TILE_Q + p->num_seqs) * p->num_q_heads;
@@ -210,6 +212,7 @@ int varlen_attn_fwd(const varlen_attn_params* p, const void* q, const void* k, c
     a.part_o = (float*)((char*)workspace + fl.part_o_ofs);
     a.part_lse = (float*)((char*)workspace + fl.part_lse_ofs);
     a.clock_probe = clock_probe_slot(0);
+    a.lean = short_batch(p) && fl.splits == 1;
     {
         ProfScope ps(VA_KERNEL_FWD, stream);
         e = va::launch_fwd(a, stream);
@@ -323,18 +326,12 @@ int varlen_attn_bwd(const varlen_attn_params* p, const void* dout, const void* q
     char* ws = (char*)workspace;
 
     hipError_t e;
-    {
+    {   // both work lists (key tiles for dK/dV, query tiles for dQ) in one launch, one workgroup each
         ProfScope ps(VA_KERNEL_SCHED, stream);
-        e = va::launch_scheduler(cu_seqlens, p->num_seqs, p->total_tokens, va::BWD_TILE_KV, va::BWD_STEP_Q,
-                                 p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL, ws + lay.kv_ofs, lay.kv,
-                                 stream);
-    }
-    if (e != hipSuccess) return hip_fail(e);
-    {
-        ProfScope ps(VA_KERNEL_SCHED, stream);
-        e = va::launch_scheduler(cu_seqlens, p->num_seqs, p->total_tokens, va::BWD_TILE_Q, va::BWD_STEP_KV,
-                                 p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q,
-                                 stream);
+        e = va::launch_scheduler_pair(cu_seqlens, p->num_seqs, p->total_tokens, va::BWD_TILE_KV, va::BWD_STEP_Q,
+                                      p->causal ? va::COST_CAUSAL_KEY : va::COST_FULL, ws + lay.kv_ofs, lay.kv,
+                                      va::BWD_TILE_Q, va::BWD_STEP_KV,
+                                      p->causal ? va::COST_CAUSAL_QUERY : va::COST_FULL, ws + lay.q_ofs, lay.q, stream);
     }
     if (e != hipSuccess) return hip_fail(e);
 

@@ -204,34 +204,46 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
 template <int D, bool CAUSAL>
 constexpr int kFwdWgsPerCu = D <= 80 ? 3 : 2;
 
-template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
-fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
-           __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
-           const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale, int S,
-           float* __restrict__ part_o, float* __restrict__ part_lse, unsigned long long* __restrict__ clock_probe) {
+// One work item: the query tile `wid` names (see xcd_item_head), all its key tiles.  `lds` is the workgroup's
+// staging memory, 5 tiles (K x3, then V x2).
+// LEAN (batches of short samples): loads past the item's last tile are not issued.  The general form
+// issues them regardless (they re-fetch the last tile into a free slot), which keeps its loop free of
+// branches and its wait counts constant; an item of one or two tiles, though, then waits for two more
+// memory round trips than it has use for, and in that regime the round trips are all there is.
+template <int D, bool CAUSAL, bool LEAN = false>
+__device__ __forceinline__ void fwd_work_item(unsigned wid, unsigned char* lds, const __bf16* __restrict__ Q,
+                                              const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+                                              __bf16* __restrict__ O, float* __restrict__ LSE,
+                                              const int32_t* __restrict__ hdr, const WorkItem* __restrict__ items,
+                                              int max_items, int T, int Hq, int Hkv, float scale, int S,
+                                              float* __restrict__ part_o, float* __restrict__ part_lse,
+                                              unsigned long long* __restrict__ clock_probe) {
     using C = FwdCfg<D>;
     using LT = LdsTile<D>;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * C::TILE];  // K x3, then V x2
 
     // S > 1: the key tiles of every query tile are split into S consecutive chunks, one workgroup
     // each, which write partial results (fp32 O and LSE per chunk) that a merge kernel combines.  Used
     // for launches too small to fill the chip (few heads, one mid-length sample).
-    const int ch = S > 1 ? (int)(blockIdx.x % S) : 0;
-    const unsigned bid = S > 1 ? blockIdx.x / S : blockIdx.x;
+    const int ch = S > 1 ? (int)(wid % S) : 0;
+    const unsigned bid = S > 1 ? wid / S : wid;
     int item, hp;
-    xcd_item_head(bid, max_items, Hq, Hkv, hdr[1], item, hp);
+    // (LEAN: always the item-major order, which is what the scheduler picks for short samples anyway; not
+    // reading it from the header lets the work item's own load start at once, next to the header's)
+    xcd_item_head(bid, max_items, Hq, Hkv, LEAN ? 1 : hdr[1], item, hp);
     // (integer division runs on the vector ALU; make the results scalar again, so that what is derived
     // from them stays in scalar registers)
     item = __builtin_amdgcn_readfirstlane(item); hp = __builtin_amdgcn_readfirstlane(hp);
-    if (item >= hdr[0]) return;
+    if (!LEAN && item >= hdr[0]) return;
     ClockProbe wg_clock;
     wg_clock.begin(clock_probe);
     // Head slots count the kv heads first, so that (with Hkv a multiple of the 8 XCDs) every XCD's L2
     // only ever sees its own kv heads.
     const int kvh = hp % Hkv;
     const int h = kvh * (Hq / Hkv) + hp / Hkv;
+    // (LEAN: an entry past the live ones is inside the list's memory, whatever it holds; it is only looked at
+    // after the check)
     const WorkItem it = items[item];
+    if (LEAN && item >= hdr[0]) return;
     // same for the whole workgroup: tell the compiler, so that everything derived stays in SGPRs
     const int sb = __builtin_amdgcn_readfirstlane(it.y), L = __builtin_amdgcn_readfirstlane(it.z - it.y),
               q0 = __builtin_amdgcn_readfirstlane(it.x - it.y);  // q0: tile start inside the sample
@@ -293,7 +305,7 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     // bookkeeping at loop entry it would put a wait for ALL outstanding loads into every iteration.
     load_tile(kbase, jb, lds0);
     load_tile(vbase, jb, lds0 + 3 * C::TILE);
-    load_tile(kbase, jb + 1, lds0 + C::TILE);
+    if (!LEAN || jb + 1 < je) load_tile(kbase, jb + 1, lds0 + C::TILE);
     bf16x8 qf[C::KS];
     {
         const __bf16* qp = Q + ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
@@ -314,12 +326,13 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     const unsigned char *iss_v = nullptr, *iss_k = nullptr;
     uint32_t iss_v_lds = 0, iss_k_lds = 0;
     bool iss_v_ragged = false, iss_k_ragged = false;
+    bool do_v = true, do_k = true;  // LEAN: whether tiles j + 1 and j + 2 exist (wave-uniform)
     auto issue = [&](int slot) {  // slot is a compile-time constant after inlining
         constexpr int NI = C::NI, HALF = (NI + 1) / 2;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            if (slot == (i < HALF ? 0 : 1)) dma.issue_one_rt(i, iss_v, iss_v_ragged, iss_v_lds, w);
-            if (slot == (i < HALF ? 2 : 3)) dma.issue_one_rt(i, iss_k, iss_k_ragged, iss_k_lds, w);
+            if (slot == (i < HALF ? 0 : 1) && (!LEAN || do_v)) dma.issue_one_rt(i, iss_v, iss_v_ragged, iss_v_lds, w);
+            if (slot == (i < HALF ? 2 : 3) && (!LEAN || do_k)) dma.issue_one_rt(i, iss_k, iss_k_ragged, iss_k_lds, w);
         }
     };
 #define VA_FWD_ITER_BEGIN()                                                                \
@@ -330,11 +343,12 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
         iss_k_ragged = ragged_sample && min(j + 2, je - 1) == last_tile;                       \
         iss_v_lds = lds0 + (3 + (vslot ^ 1)) * C::TILE;                                        \
         iss_k_lds = lds0 + (kslot == 0 ? 2 : kslot - 1) * C::TILE; /* slot (j + 2 - jb) % 3 */ \
+        if (LEAN) { do_v = j + 1 < je; do_k = j + 2 < je; }                                    \
         const unsigned char* kb = kbuf + kslot * C::TILE;                                      \
         const unsigned char* vb = vbuf + vslot * C::TILE;
-    // K(j+1) and V(j+1) must have landed; K(j+2), issued last, may stay in flight.
+    // K(j+1) and V(j+1) must have landed; K(j+2), issued last, may stay in flight (LEAN: if it was issued).
 #define VA_FWD_ITER_END()                                                                  \
-        wait_vmcnt<C::NI>();                                                                   \
+        if (!LEAN || do_k) wait_vmcnt<C::NI>(); else wait_vmcnt<0>();                          \
         wg_barrier();                                                                          \
         kslot = kslot == 2 ? 0 : kslot + 1;                                                    \
         vslot ^= 1;
@@ -413,10 +427,50 @@ fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __b
     wg_clock.end(clock_probe);
 }
 
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
+fwd_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+           __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
+           const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale, int S,
+           float* __restrict__ part_o, float* __restrict__ part_lse, unsigned long long* __restrict__ clock_probe) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * FwdCfg<D>::TILE];  // K x3, then V x2
+    fwd_work_item<D, CAUSAL>(blockIdx.x, lds, Q, K, V, O, LSE, hdr, items, max_items, T, Hq, Hkv, scale, S, part_o,
+                             part_lse, clock_probe);
+}
+
+// The same for batches of short samples only (the caller's max_seqlen says so): the LEAN form of the work
+// item.  There an item is one or two tile steps, a workgroup lives for a few microseconds, nearly all of it
+// waiting for memory round trips one after the other (measured at 64-token samples: item record, first
+// tiles, and two more for loads past the last tile), and the launch is bound by that chain and by the rate
+// at which workgroups start, not by bandwidth or arithmetic.  (A variant that starts only as many workgroups
+// as fit on the chip and lets each walk the list was measured slower than this one: the hardware handing the
+// next item to whichever CU has room is worth more than the saved workgroup starts.)
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, (kFwdWgsPerCu<D, CAUSAL>))
+fwd_kernel_lean(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+                __bf16* __restrict__ O, float* __restrict__ LSE, const int32_t* __restrict__ hdr,
+                const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale,
+                unsigned long long* __restrict__ clock_probe) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[5 * FwdCfg<D>::TILE];
+    fwd_work_item<D, CAUSAL, true>(blockIdx.x, lds, Q, K, V, O, LSE, hdr, items, max_items, T, Hq, Hkv, scale, 1,
+                                   nullptr, nullptr, clock_probe);
+}
+
 template <int D>
 static hipError_t launch_d(const FwdArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(a.max_items * a.num_q_heads * a.kv_splits)), block(256);
     auto q = (const __bf16*)a.q; auto k = (const __bf16*)a.k; auto v = (const __bf16*)a.v;
+    if (a.lean) {  // batches of short samples (see fwd_kernel_lean); never with split keys
+        if (a.causal)
+            hipLaunchKernelGGL((fwd_kernel_lean<D, true>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
+                               a.sched_hdr, a.items, (int)a.max_items, a.total_tokens, a.num_q_heads, a.num_kv_heads,
+                               a.scale, a.clock_probe);
+        else
+            hipLaunchKernelGGL((fwd_kernel_lean<D, false>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
+                               a.sched_hdr, a.items, (int)a.max_items, a.total_tokens, a.num_q_heads, a.num_kv_heads,
+                               a.scale, a.clock_probe);
+        return hipGetLastError();
+    }
     if (a.causal)
         hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, stream, q, k, v, (__bf16*)a.o, a.lse,
                            a.sched_hdr, a.items, (int)a.max_items, a.total_tokens, a.num_q_heads, a.num_kv_heads, a.scale,

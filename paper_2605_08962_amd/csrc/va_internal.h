@@ -54,6 +54,12 @@ int64_t schedule_on_host(const int32_t* cu_seqlens, int num_seqs, int total_toke
 hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows,
                             int partner_rows, CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream);
 
+// Two work lists in one launch (one workgroup each): what the backward needs.
+hipError_t launch_scheduler_pair(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows_a,
+                                 int partner_rows_a, CostMode mode_a, void* ws_a, const SchedLayout& lay_a,
+                                 int tile_rows_b, int partner_rows_b, CostMode mode_b, void* ws_b,
+                                 const SchedLayout& lay_b, hipStream_t stream);
+
 // Enqueue the check of cu_seqlens' contents: *verdict (device) = 0 if cu[0] = 0, cu never decreases and
 // cu[num_seqs] = total_tokens, else 1.
 hipError_t launch_check_cu_seqlens(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int32_t* verdict,
@@ -72,7 +78,9 @@ struct FwdArgs {
     float* part_o;    // kv_splits > 1: fp32 [kv_splits, T, Hq, D] partial outputs
     float* part_lse;  // kv_splits > 1: fp32 [kv_splits, Hq, T]
     unsigned long long* clock_probe;  // null, or 2 counters (see ClockProbe)
+    bool lean;  // batches of short samples (the caller's max_seqlen says so), kv_splits == 1: the lean kernel form
 };
+constexpr int kShortBatchMaxSeqlen = 1024;  // max_seqlen hint up to which a batch counts as "short samples only"
 constexpr int FWD_TILE_Q = 128;
 constexpr int FWD_TILE_KV = 64;
 hipError_t launch_fwd(const FwdArgs& a, hipStream_t stream);

@@ -46,12 +46,29 @@ __device__ int block_exclusive_scan(int v, int* buf, int* total) {
     return incl - v;
 }
 
+// Samples whose clamped bounds and tile offsets the kernel keeps in LDS (3 x 4 bytes each); a batch with more
+// samples reads them from global memory instead (same results, slower searches).
+constexpr int SCHED_CACHE = 8192;
+
+struct SchedJob {  // one work list
+    int R, U, mode, max_items;
+    int32_t *hdr, *tile_off;
+    WorkItem* items;
+};
+
+// One workgroup per work list (the backward builds two at a time).
 __global__ void __launch_bounds__(SCHED_THREADS)
-sched_kernel(const int32_t* __restrict__ cu, int B, int T, int max_items, int R, int U, int mode,
-             int32_t* __restrict__ hdr, int32_t* __restrict__ tile_off, WorkItem* __restrict__ items) {
+sched_kernel(const int32_t* __restrict__ cu, int B, int T, SchedJob job0, SchedJob job1) {
     __shared__ int scan_buf[SCHED_THREADS];
     __shared__ int bins[SCHED_BINS];
+    __shared__ int beg_l[SCHED_CACHE], end_l[SCHED_CACHE], toff_l[SCHED_CACHE + 1];
     __shared__ int longest;
+    const SchedJob job = blockIdx.x == 0 ? job0 : job1;
+    const int R = job.R, U = job.U, mode = job.mode;
+    int32_t* __restrict__ const hdr = job.hdr;
+    int32_t* __restrict__ const tile_off = job.tile_off;
+    WorkItem* __restrict__ const items = job.items;
+    const bool cached = B <= SCHED_CACHE;  // (uniform)
     const int t = threadIdx.x;
     if (t == 0) longest = 0;
     __syncthreads();
@@ -64,18 +81,22 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int T, int max_items, int R,
         if (s < B) {
             int begin, end;
             sched_sample_rows(cu[s], cu[s + 1], T, begin, end);
+            if (cached) { beg_l[s] = begin; end_l[s] = end; }
             const int len = end - begin;
             n = (len + R - 1) / R;
             if (len >= kXcdChunkMinLen) longest = len;  // (any such length will do: only the threshold matters)
         }
         int total;
         int ex = block_exclusive_scan(n, scan_buf, &total);
-        if (s < B) tile_off[s] = carry + ex;
+        if (s < B) {
+            tile_off[s] = carry + ex;
+            if (cached) toff_l[s] = carry + ex;
+        }
         carry += total;
     }
     // (a well-formed batch has at most max_items tiles; one that is not loses the surplus instead of
     // writing past the list)
-    const int n_items = min(carry, max_items);
+    const int n_items = min(carry, job.max_items);
     if (t == 0) {
         tile_off[B] = n_items;
         hdr[0] = n_items;
@@ -84,16 +105,30 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int T, int max_items, int R,
     for (int i = t; i < SCHED_BINS; i += SCHED_THREADS) bins[i] = 0;
     __syncthreads();  // also makes tile_off (global, written by this block) visible to the block
 
+    // the sample that holds tile idx of the batch (largest s with tile_off[s] <= idx), its rows and the tile's cost
+    auto locate = [&](int idx, int& begin, int& end, int& tile) {
+        int lo = 0, hi = B;
+        if (cached) {
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (toff_l[mid] <= idx) lo = mid; else hi = mid;
+            }
+            begin = beg_l[lo]; end = end_l[lo]; tile = idx - toff_l[lo];
+        } else {
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (tile_off[mid] <= idx) lo = mid; else hi = mid;
+            }
+            sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
+            tile = idx - tile_off[lo];
+        }
+        return sched_tile_cost(end - begin, tile, R, U, mode);
+    };
+
     // 2. histogram of costs
     for (int idx = t; idx < n_items; idx += SCHED_THREADS) {
-        int lo = 0, hi = B;  // largest s with tile_off[s] <= idx
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if (tile_off[mid] <= idx) lo = mid; else hi = mid;
-        }
-        int begin, end;
-        sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
-        atomicAdd(&bins[sched_tile_cost(end - begin, idx - tile_off[lo], R, U, mode)], 1);
+        int begin, end, tile;
+        atomicAdd(&bins[locate(idx, begin, end, tile)], 1);
     }
     __syncthreads();
 
@@ -117,25 +152,33 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int T, int max_items, int R,
 
     // 4. scatter (the order inside one cost class is arbitrary; results do not depend on it)
     for (int idx = t; idx < n_items; idx += SCHED_THREADS) {
-        int lo = 0, hi = B;
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if (tile_off[mid] <= idx) lo = mid; else hi = mid;
-        }
-        int begin, end;
-        sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
-        int tile = idx - tile_off[lo];
-        int pos = atomicAdd(&bins[sched_tile_cost(end - begin, tile, R, U, mode)], 1);
+        int begin, end, tile;
+        const int pos = atomicAdd(&bins[locate(idx, begin, end, tile)], 1);
         items[pos] = make_int4(begin + tile * R, begin, end, tile);
     }
 }
 
+static SchedJob make_job(int tile_rows, int partner_rows, CostMode mode, void* ws, const SchedLayout& lay) {
+    char* base = (char*)ws;
+    return SchedJob{tile_rows, partner_rows, (int)mode, (int)lay.max_items, (int32_t*)base,
+                    (int32_t*)(base + lay.tile_off_ofs), (WorkItem*)(base + lay.items_ofs)};
+}
+
 hipError_t launch_scheduler(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows,
                             int partner_rows, CostMode mode, void* ws, const SchedLayout& lay, hipStream_t stream) {
-    char* base = (char*)ws;
+    const SchedJob job = make_job(tile_rows, partner_rows, mode, ws, lay);
     hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs, total_tokens,
-                       (int)lay.max_items, tile_rows, partner_rows, (int)mode, (int32_t*)base,
-                       (int32_t*)(base + lay.tile_off_ofs), (WorkItem*)(base + lay.items_ofs));
+                       job, job);
+    return hipGetLastError();
+}
+
+hipError_t launch_scheduler_pair(const int32_t* cu_seqlens, int num_seqs, int total_tokens, int tile_rows_a,
+                                 int partner_rows_a, CostMode mode_a, void* ws_a, const SchedLayout& lay_a,
+                                 int tile_rows_b, int partner_rows_b, CostMode mode_b, void* ws_b,
+                                 const SchedLayout& lay_b, hipStream_t stream) {
+    hipLaunchKernelGGL(sched_kernel, dim3(2), dim3(SCHED_THREADS), 0, stream, cu_seqlens, num_seqs, total_tokens,
+                       make_job(tile_rows_a, partner_rows_a, mode_a, ws_a, lay_a),
+                       make_job(tile_rows_b, partner_rows_b, mode_b, ws_b, lay_b));
     return hipGetLastError();
 }
 

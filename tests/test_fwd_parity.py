@@ -168,3 +168,24 @@ def test_self_similar_and_shifted_keys(D, causal):
     _check_full(w, allow_output_rounding=True)
     w.k = W.f32_to_bf16_bits(W.bf16_bits_to_f32(w.q) + 3.0)
     _check_full(w, allow_output_rounding=True)
+
+
+@pytest.mark.parametrize("D", [64, 80, 96, 128])
+@pytest.mark.parametrize("causal", [False, True])
+def test_max_seqlen_hint_selects_the_lean_kernel_and_changes_nothing(D, causal):
+    """0 < max_seqlen <= 1024 makes the forward take its lean form (no loads past a tile list's end).  Same
+    arithmetic in the same order: the results are bit-identical to the call without the hint, whether the hint
+    is right, generous, or WRONG (a sample longer than promised); and they match the oracle."""
+    import oracle
+    from paper_2605_08962_amd import binding
+    lengths = [64, 1, 300, 0, 129, 128, 63, 65, 700, 2, 256, 1000]
+    w = W.make_custom(lengths, 4, 2, D, causal, seed=640 + D + causal)
+    d = upload(w)
+    ref_o, ref_lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], causal, w.scale, kv_splits=1)
+    for hint in (1000, 1024, 100, 1):                       # exact, generous, wrong, absurdly wrong
+        o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], causal, w.scale, kv_splits=1, max_seqlen=hint)
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref_o) and torch.equal(lse, ref_lse), f"hint {hint}"
+    ro, rlse = oracle.fwd(w.f32("q"), w.f32("k"), w.f32("v"), w.cu_seqlens, causal, w.scale)
+    assert_close("O", to_f64(o), ro, allow_output_rounding=True)
+    assert float(np.abs(to_f64(lse) - rlse).max()) <= LSE_ABS
