@@ -8,15 +8,16 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvarlen_attn.so")
 # (source, object name, extra flags).  va_bwd.hip is built in three parts: the head_dim 128 dK/dV and dQ
-# kernels get their own instruction-scheduling strategy (measured faster there, slower elsewhere), and
-# dK/dV at 128 is told to let MFMAs write S and dP into ordinary vector registers: it runs one wave per
-# SIMD on more than 256 registers, and the default puts every MFMA result into the accumulation half of
-# the register file, from where the vector ALU needs a copy per register (64 per step; 5 % of its time).
+# kernels get their own instruction-scheduling strategy (measured faster there: dK/dV 7 %, the two-workgroup dQ
+# kernel 1-7 %; slower for the other head sizes), and dK/dV at 128 is told to let MFMAs write S and dP into
+# ordinary vector registers: it runs one wave per SIMD on more than 256 registers, and the default puts every
+# MFMA result into the accumulation half of the register file, from where the vector ALU needs a copy per
+# register (64 per step; 5 % of its time).
 SOURCES = [("va_api.hip", "va_api.o", []), ("va_sched.hip", "va_sched.o", []), ("va_fwd.hip", "va_fwd.o", []),
            ("va_bwd.hip", "va_bwd.o", ["-DVA_BWD_PART=0"]),
            ("va_bwd.hip", "va_bwd_dkdv128.o", ["-DVA_BWD_PART=1", "-mllvm", "-amdgpu-sched-strategy=iterative-ilp",
                                                "-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
-           ("va_bwd.hip", "va_bwd_dq128.o", ["-DVA_BWD_PART=2", "-mllvm", "-amdgpu-sched-strategy=max-memory-clause"]),
+           ("va_bwd.hip", "va_bwd_dq128.o", ["-DVA_BWD_PART=2", "-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]),
            ("va_partition.hip", "va_partition.o", []), ("va_merge.hip", "va_merge.o", [])]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form v_pk_*_f32 from float code.
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores use a finite

@@ -11,7 +11,9 @@
 //            (contraction over query rows).
 //   dq     : one workgroup per (128-row query tile, query head); loops over 64-row key steps;
 //            S^T = K Q^T is kept with one QUERY per lane (as in the forward), so that dS^T is the
-//            B operand of dQ^T += K^T dS^T (contraction over key rows).
+//            B operand of dQ^T += K^T dS^T (contraction over key rows).  Two forms: dq_kernel (head_dim 64
+//            and 80: phases, four LDS stages) and dq_kernel_2wg (96 and 128: operands read at use, two
+//            stages, so that two workgroups fit a CU).
 // Splitting the backward this way needs no atomics and no fp32 dQ buffer, and the result does not
 // depend on scheduling order; it recomputes S and dP once more than a fused kernel would.
 //
@@ -20,8 +22,8 @@
 //
 // The file is compiled three times (VA_BWD_PART): part 0 holds everything but the head_dim 128 dK/dV
 // and dQ kernels, which parts 1 and 2 build under a different instruction-scheduling strategy of the
-// compiler (measured 7 % and 4 % faster there, slower for the other head sizes; part 1 also with MFMA
-// results in ordinary vector registers, see build.py).
+// compiler (measured 7 % and up to 7 % faster there, slower for the other head sizes; part 1 also with
+// MFMA results in ordinary vector registers, see build.py).
 #include "va_device.h"
 #include "va_internal.h"
 
@@ -888,6 +890,209 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
     wg_clock.end(clock_probe);
 }
 
+// ------------------------------------------------------------------------------------------------
+// dQ for head_dim 96 / 128 when the work items are short (causal batches of a few thousand tokens per
+// sample): two workgroups per CU.
+//
+// dq_kernel above keeps three sets of operands in flight (its phases) and four LDS stages, which at these
+// head sizes takes 400 registers and 128 KB: one workgroup per CU.  Its start (Q, dO, O, LSE, three stages of
+// K/V, all waited for) and its end (stores) then run with nothing beside them, and a query tile under the
+// causal mask has only (q0 + 128) / 64 key steps to spread that over: measured, the fixed cost of an item is
+// about 8 of its steps, and the matrix pipes are 41 % busy on the LLM batch against 60 % elsewhere.
+// This form reads each operand right before its MFMAs (32 keys of S and dP live at a time), double-buffers
+// K/V in two LDS stages (64 KB) and fits 256 registers, so two workgroups share a CU and one's start and end
+// hide behind the other's steps.  Same arithmetic per element as dq_kernel (P, dP - Delta, dS rounded to
+// bf16, hi + lo where rows can have few keys).  Measured against dq_kernel at head_dim 128: the LLM batch's dQ
+// 2.23 -> 1.82 ms, 16384-token causal samples 6.33 -> 5.52 ms, 16384-token samples without the mask 5.73 = 5.73 ms,
+// 512-token causal samples 0.63 -> 0.47 ms; at head_dim 96 20-26 % faster.  It is the dQ kernel of head_dim 96 and
+// 128 (the operands that only the matrix cores touch are left to the compiler here: parked in the accumulation
+// half they pin 128 of the 256 registers there and the vector half spills).
+// ------------------------------------------------------------------------------------------------
+template <int D, bool CAUSAL, bool MASKED>
+__device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const unsigned char* vt,
+                                              const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
+                                              const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
+                                              f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
+                                              int kv0, int qrow, int L, int hh, bool lo) {
+    using C = BwdCfg<D>;
+    constexpr int ROWB = C::T::ROWB;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        if (b) __builtin_amdgcn_sched_barrier(0);  // keep the second block's operand reads behind the first block
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = ndelta; }
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            bf16x8 ak = *(const bf16x8*)(kt + aaddr[ks] + b * 32 * ROWB);
+            s = mfma32(ak, qf[ks], s);
+            bf16x8 av = *(const bf16x8*)(vt + aaddr[ks] + b * 32 * ROWB);
+            dp = mfma32(av, dof[ks], dp);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float p = fast_exp2(__builtin_fmaf(s[r], c2, -lse2));
+            if (MASKED) {
+                const int kv = kv0 + 32 * b + 8 * (r / 4) + 4 * hh + (r % 4);
+                const bool ok = kv < L && qrow < L && (!CAUSAL || kv <= qrow);
+                p = ok ? p : 0.f;
+            }
+            dp[r] *= p;
+        }
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const bf16x8 dsb = pack_regs(dp, st);
+            const int rowoff = (32 * b + 16 * st) * ROWB;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db) {
+                bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
+                dqacc[db] = mfma32(ak, dsb, dqacc[db]);
+            }
+        }
+        if (MASKED && lo) {  // wave-uniform: the lo parts of dS, in a pass of their own (as in dq_kernel)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const bf16x8 dsl = pack_regs_lo(dp, st, pack_regs(dp, st));
+                const int rowoff = (32 * b + 16 * st) * ROWB;
+#pragma unroll
+                for (int db = 0; db < C::DB; ++db) {
+                    bf16x8 ak = cat4(lds_read_tr(kt + rowoff + taddr[db][0]), lds_read_tr(kt + rowoff + taddr[db][1]));
+                    dqacc[db] = mfma32(ak, dsl, dqacc[db]);
+                }
+            }
+        }
+    }
+}
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, 2)
+dq_kernel_2wg(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+              const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
+              float2* __restrict__ stats, __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr,
+              const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale,
+              unsigned long long* __restrict__ clock_probe) {
+    using C = BwdCfg<D>;
+    using LT = LdsTile<D>;
+    constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
+
+    int item, hp;
+    xcd_item_head(blockIdx.x, max_items, Hq, Hkv, hdr[1], item, hp);
+    item = __builtin_amdgcn_readfirstlane(item); hp = __builtin_amdgcn_readfirstlane(hp);
+    if (item >= hdr[0]) return;
+    ClockProbe wg_clock;
+    wg_clock.begin(clock_probe);
+    const int kvh = hp % Hkv;
+    const int h = kvh * (Hq / Hkv) + hp / Hkv;
+    const WorkItem it = items[item];
+    const int sb = __builtin_amdgcn_readfirstlane(it.y), L = __builtin_amdgcn_readfirstlane(it.z - it.y),
+              q0 = __builtin_amdgcn_readfirstlane(it.x - it.y);
+    const int tid = threadIdx.x, w = uniform_wave_id(), l = tid & 63, ln = l & 31, hh = l >> 5;
+    const int qrow = q0 + 32 * w + ln;
+    const bool qvalid = qrow < L;
+
+    const int kv_end = CAUSAL ? min(L, q0 + BWD_TILE_Q) : L;
+    const int nsteps = (kv_end + BWD_STEP_KV - 1) / BWD_STEP_KV;
+    const int n_plain = CAUSAL ? min(L, q0 + 1) / BWD_STEP_KV : L / BWD_STEP_KV;
+    const unsigned char* kbase = (const unsigned char*)(K + ((size_t)sb * Hkv + kvh) * D);
+    const unsigned char* vbase = (const unsigned char*)(V + ((size_t)sb * Hkv + kvh) * D);
+    const uint32_t row_bytes = (uint32_t)Hkv * D * 2;
+    TileDma<D, 64> dma;
+    dma.init(row_bytes, L, w, l);
+    const uint32_t lds0 = lds_address(lds);
+    const int64_t step_bytes = (int64_t)BWD_STEP_KV * row_bytes;
+    const bool ragged_sample = (L % BWD_STEP_KV) != 0;
+    const int last_step = (L + BWD_STEP_KV - 1) / BWD_STEP_KV - 1;  // the one holding the sample's end
+    // loads of step j into stage j % 2; a step past the item's last one is not loaded
+    auto issue_step = [&](int j) {
+        if (j < nsteps) {
+            const bool ragged = ragged_sample && j == last_step;
+            const uint32_t st = lds0 + (j & 1) * STAGE;
+            dma.issue_tile(kbase + (size_t)j * step_bytes, ragged, st, w);
+            dma.issue_tile(vbase + (size_t)j * step_bytes, ragged, st + C::TILE, w);
+        }
+    };
+    int aaddr[C::KS], taddr[C::DB][2];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) aaddr[ks] = LT::off(ln, 2 * ks + hh);
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) {
+        taddr[db][0] = LT::tr_off(l, 0, db);
+        taddr[db][1] = LT::tr_off(l, 8, db);
+    }
+
+    issue_step(0);
+    bf16x8 qf[C::KS], dof[C::KS];
+    float lse2 = 0.f, ndelta = 0.f;  // ndelta = -Delta
+    {
+        const size_t off = ((size_t)(sb + (qvalid ? qrow : 0)) * Hq + h) * D + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            bf16x8 z = {};
+            qf[ks] = qvalid ? *(const bf16x8*)(Q + off + 16 * ks) : z;
+            dof[ks] = qvalid ? *(const bf16x8*)(dO + off + 16 * ks) : z;
+        }
+        // row statistics of this lane's row, as in dq_kernel (same order of operations)
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            bf16x8 z = {};
+            const bf16x8 of = qvalid ? *(const bf16x8*)(O + off + 16 * ks) : z;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)dof[ks][e], (float)of[e], part);
+        }
+        ndelta = -xhalf_sum(part);
+        if (qvalid) {
+            lse2 = LSE[(size_t)h * T + sb + qrow] * kLog2e;
+            if (hh == 0) stats[(size_t)h * T + sb + qrow] = make_float2(lse2, ndelta);
+        }
+    }
+    // (everything waited for here, once: see the forward kernel for why the register loads must not be left
+    // pending at loop entry)
+    wait_vmcnt<0>();
+
+    f32x16 dqacc[C::DB];
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dqacc[db][r] = 0.f;
+    const float c2 = scale * kLog2e;
+    const bool lo_steps = !CAUSAL || q0 == 0;
+
+    // Step j: its loads (issued during step j - 1) have landed; the barrier publishes them and tells that every
+    // wave is done with step j - 1, whose stage the loads of step j + 1 may now overwrite.
+    auto step = [&](int j, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        wait_vmcnt<0>();
+        wg_barrier();
+        issue_step(j + 1);
+        const unsigned char* st = lds + (j & 1) * STAGE;
+        dq_plain_step<D, CAUSAL, MASKED>(st, st + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta,
+                                         j * BWD_STEP_KV, qrow, L, hh, lo_steps);
+    };
+    int j = 0;
+    for (; j < n_plain; ++j) step(j, std::false_type{});
+    for (; j < nsteps; ++j) step(j, std::true_type{});
+    wait_vmcnt<0>();
+
+    if (qvalid) {
+        __bf16* dqp = dQ + ((size_t)(sb + qrow) * Hq + h) * D;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d0 = 32 * db + 8 * r4 + 4 * hh;
+                if (d0 < D) {
+                    bf16x4 a;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[e] = (__bf16)(dqacc[db][4 * r4 + e] * scale);
+                    *(bf16x4*)(dqp + d0) = a;
+                }
+            }
+    }
+    wg_clock.end(clock_probe);
+}
+
 template <int D>
 static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(a.max_items_q * a.num_q_heads)), block(256);
@@ -895,14 +1100,25 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     auto dO = (const __bf16*)a.dout;
     auto o = (const __bf16*)a.o;
     auto st = (float2*)a.stats;
-    if (a.causal)
-        hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
-                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens, a.num_q_heads,
-                           a.num_kv_heads, a.scale, a.clock_probe_dq);
-    else
-        hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
-                           (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens, a.num_q_heads,
-                           a.num_kv_heads, a.scale, a.clock_probe_dq);
+    if constexpr (D > 80) {  // (measured equal or faster than dq_kernel on every shape tried, see dq_kernel_2wg)
+        if (a.causal)
+            hipLaunchKernelGGL((dq_kernel_2wg<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+                               (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
+                               a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
+        else
+            hipLaunchKernelGGL((dq_kernel_2wg<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+                               (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
+                               a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
+    } else {
+        if (a.causal)
+            hipLaunchKernelGGL((dq_kernel<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+                               (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
+                               a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
+        else
+            hipLaunchKernelGGL((dq_kernel<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+                               (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
+                               a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
+    }
     return hipGetLastError();
 }
 
