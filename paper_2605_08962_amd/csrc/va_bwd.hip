@@ -906,7 +906,8 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 // 2.23 -> 1.82 ms, 16384-token causal samples 6.33 -> 5.52 ms, 16384-token samples without the mask 5.73 = 5.73 ms,
 // 512-token causal samples 0.63 -> 0.47 ms; at head_dim 96 20-26 % faster.  It is the dQ kernel of head_dim 96 and
 // 128 (the operands that only the matrix cores touch are left to the compiler here: parked in the accumulation
-// half they pin 128 of the 256 registers there and the vector half spills).
+// half they pin 128 of the 256 registers there and the vector half spills).  At head_dim 64 and 80 the phased
+// dq_kernel stays: this form at three workgroups per CU measured 2 % slower at 64 and spills at 80.
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASKED>
 __device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const unsigned char* vt,
