@@ -29,6 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 CSRC = os.path.join(ROOT, "paper_2605_08962_amd", "csrc")
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.json")
 KERNEL_SYMBOL = {"fwd": "fwd_kernel", "dkdv": "dkdv_kernel", "dq": "dq_kernel"}
+KERNEL_SYMBOLS_ALL = ("fwd_kernel_lean", "fwd_kernel", "dkdv_kernel", "dq_kernel_2wg", "dq_kernel")
 
 
 def kernel_source_hash():
@@ -43,7 +44,10 @@ def kernel_source_hash():
 
 
 def _instance(kernel, head_dim, causal):
-    return f"{KERNEL_SYMBOL[kernel]}<{head_dim}, {'true' if causal else 'false'}>"
+    sym = KERNEL_SYMBOL[kernel]
+    if kernel == "dq" and head_dim > 80:
+        sym = "dq_kernel_2wg"           # head_dim 96 / 128 have a dQ kernel of their own
+    return f"{sym}<{head_dim}, {'true' if causal else 'false'}>"
 
 
 def measured_traffic(kernel, head_dim, causal):
@@ -87,7 +91,7 @@ def record_traffic(paths):
         factor[counter] = float(1 << 30) / (largest_copy[counter] * 1024.0)   # true bytes per counted byte
     kernels = {}
     for (counter, name), (v, ids) in val.items():
-        for sym in KERNEL_SYMBOL.values():
+        for sym in KERNEL_SYMBOLS_ALL:
             # demangled "va::fwd_kernel<64, false>(...)", or, where the profiler's demangler gave up, the
             # mangled "_ZN2va11dkdv_kernelILi64ELb0EEEv..."
             m = re.search(r"va::%s<(\d+), (true|false)>" % sym, name)
@@ -99,10 +103,11 @@ def record_traffic(paths):
                     continue
                 inst = f"{sym}<{m.group(1)}, {'true' if m.group(2) == '1' else 'false'}>"
             if counter not in factor:
-                continue
+                break
             e = kernels.setdefault(inst, {})
             e[counter.lower() + "_kib_per_dispatch"] = round(v / len(ids), 1)
             e["dispatches"] = len(ids)
+            break
     for inst, e in kernels.items():
         if "fetch_size_kib_per_dispatch" in e and "write_size_kib_per_dispatch" in e:
             e["bytes"] = int(1024.0 * (e["fetch_size_kib_per_dispatch"] * factor["FETCH_SIZE"] +

@@ -1005,12 +1005,19 @@ dq_kernel_2wg(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const 
     const bool ragged_sample = (L % BWD_STEP_KV) != 0;
     const int last_step = (L + BWD_STEP_KV - 1) / BWD_STEP_KV - 1;  // the one holding the sample's end
     // loads of step j into stage j % 2; a step past the item's last one is not loaded
+    // (the ragged step in a branch of its own, with the flag a constant on either side: a select between the two
+    // offset tables on a run-time flag makes the compiler index them through memory, and it then moves them into
+    // LDS, at 32 bytes per lane: bank conflicts in every load that reads them)
     auto issue_step = [&](int j) {
         if (j < nsteps) {
-            const bool ragged = ragged_sample && j == last_step;
             const uint32_t st = lds0 + (j & 1) * STAGE;
-            dma.issue_tile(kbase + (size_t)j * step_bytes, ragged, st, w);
-            dma.issue_tile(vbase + (size_t)j * step_bytes, ragged, st + C::TILE, w);
+            if (ragged_sample && j == last_step) {
+                dma.issue_tile(kbase + (size_t)j * step_bytes, true, st, w);
+                dma.issue_tile(vbase + (size_t)j * step_bytes, true, st + C::TILE, w);
+            } else {
+                dma.issue_tile(kbase + (size_t)j * step_bytes, false, st, w);
+                dma.issue_tile(vbase + (size_t)j * step_bytes, false, st + C::TILE, w);
+            }
         }
     };
     int aaddr[C::KS], taddr[C::DB][2];
@@ -1058,7 +1065,12 @@ dq_kernel_2wg(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) dqacc[db][r] = 0.f;
     const float c2 = scale * kLog2e;
-    const bool lo_steps = !CAUSAL || q0 == 0;
+    // causal: only a sample's first rows hold few terms.  Without the mask every masked step (the one holding the
+    // sample's end) carries lo parts; the flag is hidden from the compiler all the same, so that the lo pass stays
+    // behind a branch of its own: folded into the step it costs the kernel 10 registers it does not have.
+    int always = 1;
+    asm volatile("" : "+s"(always));
+    const bool lo_steps = CAUSAL ? q0 == 0 : always != 0;
 
     // Step j: its loads (issued during step j - 1) have landed; the barrier publishes them and tells that every
     // wave is done with step j - 1, whose stage the loads of step j + 1 may now overwrite.
