@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 CSRC = os.path.join(ROOT, "paper_2605_08962_amd", "csrc")
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.json")
 KERNEL_SYMBOL = {"fwd": "fwd_kernel", "dkdv": "dkdv_kernel", "dq": "dq_kernel"}
-KERNEL_SYMBOLS_ALL = ("fwd_kernel_lean", "fwd_kernel", "dkdv_kernel", "dq_kernel_2wg", "dq_kernel")
+KERNEL_SYMBOLS_ALL = ("fwd_kernel_lean", "fwd_kernel", "dkdv_kernel", "dq_kernel_direct", "dq_kernel")
 
 
 def kernel_source_hash():
@@ -45,8 +45,8 @@ def kernel_source_hash():
 
 def _instance(kernel, head_dim, causal):
     sym = KERNEL_SYMBOL[kernel]
-    if kernel == "dq" and head_dim > 80:
-        sym = "dq_kernel_2wg"           # head_dim 96 / 128 have a dQ kernel of their own
+    if kernel == "dq" and head_dim != 80:
+        sym = "dq_kernel_direct"        # head_dim 80 alone keeps the phased dQ kernel
     return f"{sym}<{head_dim}, {'true' if causal else 'false'}>"
 
 

@@ -11,9 +11,9 @@
 //            (contraction over query rows).
 //   dq     : one workgroup per (128-row query tile, query head); loops over 64-row key steps;
 //            S^T = K Q^T is kept with one QUERY per lane (as in the forward), so that dS^T is the
-//            B operand of dQ^T += K^T dS^T (contraction over key rows).  Two forms: dq_kernel (head_dim 64
-//            and 80: phases, four LDS stages) and dq_kernel_2wg (96 and 128: operands read at use, two
-//            stages, so that two workgroups fit a CU).
+//            B operand of dQ^T += K^T dS^T (contraction over key rows).  Two forms: dq_kernel (head_dim 80:
+//            phases, four LDS stages) and dq_kernel_direct (64, 96 and 128: operands read at use, two
+//            stages, more workgroups per CU).
 // Splitting the backward this way needs no atomics and no fp32 dQ buffer, and the result does not
 // depend on scheduling order; it recomputes S and dP once more than a fused kernel would.
 //
@@ -891,23 +891,24 @@ dq_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf
 }
 
 // ------------------------------------------------------------------------------------------------
-// dQ for head_dim 96 / 128 when the work items are short (causal batches of a few thousand tokens per
-// sample): two workgroups per CU.
+// dQ with the operands read right before their MFMAs: the dQ kernel of head_dim 64, 96 and 128.
 //
-// dq_kernel above keeps three sets of operands in flight (its phases) and four LDS stages, which at these
-// head sizes takes 400 registers and 128 KB: one workgroup per CU.  Its start (Q, dO, O, LSE, three stages of
-// K/V, all waited for) and its end (stores) then run with nothing beside them, and a query tile under the
-// causal mask has only (q0 + 128) / 64 key steps to spread that over: measured, the fixed cost of an item is
-// about 8 of its steps, and the matrix pipes are 41 % busy on the LLM batch against 60 % elsewhere.
-// This form reads each operand right before its MFMAs (32 keys of S and dP live at a time), double-buffers
-// K/V in two LDS stages (64 KB) and fits 256 registers, so two workgroups share a CU and one's start and end
-// hide behind the other's steps.  Same arithmetic per element as dq_kernel (P, dP - Delta, dS rounded to
-// bf16, hi + lo where rows can have few keys).  Measured against dq_kernel at head_dim 128: the LLM batch's dQ
-// 2.23 -> 1.82 ms, 16384-token causal samples 6.33 -> 5.52 ms, 16384-token samples without the mask 5.73 = 5.73 ms,
-// 512-token causal samples 0.63 -> 0.47 ms; at head_dim 96 20-26 % faster.  It is the dQ kernel of head_dim 96 and
-// 128 (the operands that only the matrix cores touch are left to the compiler here: parked in the accumulation
-// half they pin 128 of the 256 registers there and the vector half spills).  At head_dim 64 and 80 the phased
-// dq_kernel stays: this form at three workgroups per CU measured 2 % slower at 64 and spills at 80.
+// dq_kernel above keeps three sets of operands in flight (its phases) and four LDS stages.  At head_dim 96 and
+// 128 that takes 400 registers and 128 KB: one workgroup per CU, whose start (Q, dO, O, LSE, three stages of
+// K/V, all waited for) and end (stores) then run with nothing beside them; a query tile under the causal mask
+// has only (q0 + 128) / 64 key steps to spread that over: measured, the fixed cost of an item was about 8 of
+// its steps, and the matrix pipes were 41 % busy on the LLM batch against 60 % elsewhere.
+// This form keeps 32 keys of S and dP live at a time, double-buffers K/V in two LDS stages and fits 256
+// registers at head_dim 128 (150 at 64), so two (three at 64) workgroups share a CU and one's start and end
+// hide behind the others' steps.  Same arithmetic per element as dq_kernel (P, dP - Delta, dS rounded to
+// bf16, hi + lo where rows can have few keys).  Measured against dq_kernel:
+//   head_dim 128: the LLM batch's dQ 2.23 -> 1.79 ms, 16384-token causal samples 6.33 -> 5.33 ms, the same
+//     without the mask 5.73 -> 5.24 ms, 512-token causal samples 0.63 -> 0.44 ms; head_dim 96: 20-26 % faster;
+//   head_dim 64: the ViT batch's dQ 3.89 -> 3.81 ms, batches of 64..1024-token samples 9-15 % faster;
+//   head_dim 80: slower (32.6 against 30.6 ms on the long/short mix; its 20 KB tiles and three partly masked
+//     loads per tile leave it short of registers at three workgroups per CU), so head_dim 80 keeps dq_kernel.
+// (The operands that only the matrix cores touch are left to the compiler here: parked in the accumulation
+// half they pin 128 of the 256 registers there and the vector half spills.)
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASKED>
 __device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const unsigned char* vt,
@@ -966,8 +967,8 @@ __device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const uns
 }
 
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, 2)
-dq_kernel_2wg(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+__global__ void __launch_bounds__(256, (D <= 80 ? 3 : 2))
+dq_kernel_direct(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
               const __bf16* __restrict__ dO, const __bf16* __restrict__ O, const float* __restrict__ LSE,
               float2* __restrict__ stats, __bf16* __restrict__ dQ, const int32_t* __restrict__ hdr,
               const WorkItem* __restrict__ items, int max_items, int T, int Hq, int Hkv, float scale,
@@ -975,6 +976,8 @@ dq_kernel_2wg(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const 
     using C = BwdCfg<D>;
     using LT = LdsTile<D>;
     constexpr int STAGE = 2 * C::TILE;  // K tile, V tile
+    // two LDS stages: step j + 1 loads while step j computes (a third stage, tried at head_dim 64, was slower:
+    // 16 more registers for nothing that the other workgroups on the CU do not already cover)
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
 
     int item, hp;
@@ -1113,13 +1116,13 @@ static hipError_t launch_dq_d(const BwdArgs& a, hipStream_t stream) {
     auto dO = (const __bf16*)a.dout;
     auto o = (const __bf16*)a.o;
     auto st = (float2*)a.stats;
-    if constexpr (D > 80) {  // (measured equal or faster than dq_kernel on every shape tried, see dq_kernel_2wg)
+    if constexpr (D != 80) {  // (head_dim 80 keeps the phased dq_kernel: see dq_kernel_direct)
         if (a.causal)
-            hipLaunchKernelGGL((dq_kernel_2wg<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+            hipLaunchKernelGGL((dq_kernel_direct<D, true>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
                                (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
                                a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
         else
-            hipLaunchKernelGGL((dq_kernel_2wg<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
+            hipLaunchKernelGGL((dq_kernel_direct<D, false>), grid, block, 0, stream, q, k, v, dO, o, a.lse, st,
                                (__bf16*)a.dq, a.sched_hdr_q, a.items_q, (int)a.max_items_q, a.total_tokens,
                                a.num_q_heads, a.num_kv_heads, a.scale, a.clock_probe_dq);
     } else {
