@@ -92,6 +92,28 @@ def test_packed_equals_alone():
         assert torch.equal(dq1, dq[a:b]) and torch.equal(dk1, dk[a:b]) and torch.equal(dv1, dv[a:b])
 
 
+@pytest.mark.parametrize("D", [64, 80, 96, 128])
+@pytest.mark.parametrize("causal", [False, True])
+def test_max_seqlen_hint_changes_nothing(D, causal):
+    """max_seqlen is a hint that nothing is sized by: the gradients are bit-identical to those of the call
+    without it, whether the hint is right, generous, or wrong (a sample longer than promised); and they match
+    the oracle."""
+    from paper_2605_08962_amd import binding
+    lengths = [64, 1, 300, 0, 129, 128, 63, 65, 700, 2, 256, 1000, 127, 191, 192, 193]
+    w = W.make_custom(lengths, 4, 2, D, causal, seed=650 + D + causal, with_dout=True)
+    print(f"case {w.name} seed={w.seed} D={D} causal={causal}", flush=True)
+    d = upload(w)
+    o, lse = binding.varlen_attn_fwd(d["q"], d["k"], d["v"], d["cu"], causal, w.scale)
+    ref = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], causal, w.scale)
+    for hint in (1000, 1024, 100, 1):                       # exact, generous, wrong, absurdly wrong
+        got = binding.varlen_attn_bwd(d["dout"], d["q"], d["k"], d["v"], o, lse, d["cu"], causal, w.scale,
+                                      max_seqlen=hint)
+        torch.cuda.synchronize()
+        assert all(torch.equal(x, y) for x, y in zip(got, ref)), f"hint {hint}"
+    assert_gradients_close(w.name, tuple(to_f64(x) for x in got), w.f32("q"), w.f32("k"), w.f32("v"), w.f32("dout"),
+                           w.cu_seqlens, causal, w.scale, to_f64(o), allow_output_rounding=True)
+
+
 def test_deterministic():
     from paper_2605_08962_amd import binding
     w = W.make_custom([700, 130], 8, 2, 128, True, seed=81, with_dout=True)
