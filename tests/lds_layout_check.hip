@@ -64,7 +64,10 @@ static int check_work_order() {
                 int item, hp;
                 va::xcd_item_head(bid, n, heads, kv, chunk, item, hp);
                 if (item < 0 || item >= n || hp < 0 || hp >= heads || !seen.insert({item, hp}).second) ++bad;
-                if (kv % 8 == 0 && (hp % kv) % 8 != (int)(bid % 8)) ++bad;  // the kv head stays on its XCD
+                // chunked order: the kv head stays on its XCD; item-major order: the slots of item i are those
+                // rotated by i, so that every XCD meets every head
+                const int slot = chunk == 1 ? ((hp - item) % heads + heads) % heads : hp;
+                if (kv % 8 == 0 && (slot % kv) % 8 != (int)(bid % 8)) ++bad;
             }
             if (bad) std::printf("work order n=%d heads=%d kv=%d chunk=%d: %d errors\n", n, heads, kv, chunk, bad);
         }
