@@ -29,26 +29,36 @@ SchedLayout sched_layout(int64_t total_tokens, int64_t num_seqs, int tile_rows) 
 }
 
 // Exclusive scan of one value per thread over the block; returns the exclusive prefix and
-// writes the block total to *total.  `buf` holds SCHED_THREADS ints.
+// writes the block total to *total.  `buf` holds SCHED_THREADS ints (the first 16 are used).
+// Inside a wave the scan runs on lane shuffles; the 16 wave totals meet in LDS (two barriers in all, where a
+// scan through LDS alone takes twenty: at a few thousand samples the scans were most of this kernel's time).
 __device__ int block_exclusive_scan(int v, int* buf, int* total) {
-    const int t = threadIdx.x;
-    buf[t] = v;
-    __syncthreads();
-    for (int d = 1; d < SCHED_THREADS; d <<= 1) {
-        int add = (t >= d) ? buf[t - d] : 0;
-        __syncthreads();
-        buf[t] += add;
-        __syncthreads();
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
     }
-    int incl = buf[t];
-    *total = buf[SCHED_THREADS - 1];
+    if (lane == 63) buf[wave] = incl;
     __syncthreads();
-    return incl - v;
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < SCHED_THREADS / 64; ++w) {
+        const int x = buf[w];
+        before += w < wave ? x : 0;
+        all += x;
+    }
+    *total = all;
+    __syncthreads();  // buf may be refilled by the next scan
+    return before + incl - v;
 }
 
-// Samples whose clamped bounds and tile offsets the kernel keeps in LDS (3 x 4 bytes each); a batch with more
-// samples reads them from global memory instead (same results, slower searches).
+// Samples whose clamped bounds and tile offsets the kernel keeps in LDS (3 x 4 bytes each).  A batch with up to
+// three times as many keeps the tile offsets there, which is what the per-tile searches walk, and reads the
+// bounds of the sample found from cu_seqlens; beyond that the searches read the workspace (same results, slower).
 constexpr int SCHED_CACHE = 8192;
+constexpr int SCHED_CACHE_OFFSETS = 3 * SCHED_CACHE;
 
 struct SchedJob {  // one work list
     int R, U, mode, max_items;
@@ -61,14 +71,18 @@ __global__ void __launch_bounds__(SCHED_THREADS)
 sched_kernel(const int32_t* __restrict__ cu, int B, int T, SchedJob job0, SchedJob job1) {
     __shared__ int scan_buf[SCHED_THREADS];
     __shared__ int bins[SCHED_BINS];
-    __shared__ int beg_l[SCHED_CACHE], end_l[SCHED_CACHE], toff_l[SCHED_CACHE + 1];
+    __shared__ int cache_l[3 * SCHED_CACHE + 1];
     __shared__ int longest;
     const SchedJob job = blockIdx.x == 0 ? job0 : job1;
     const int R = job.R, U = job.U, mode = job.mode;
     int32_t* __restrict__ const hdr = job.hdr;
     int32_t* __restrict__ const tile_off = job.tile_off;
     WorkItem* __restrict__ const items = job.items;
-    const bool cached = B <= SCHED_CACHE;  // (uniform)
+    const bool cached = B <= SCHED_CACHE;                              // (uniform) bounds and offsets in LDS
+    const bool cached_offsets = !cached && B <= SCHED_CACHE_OFFSETS;   // (uniform) offsets only
+    int* const beg_l = cache_l;
+    int* const end_l = cache_l + SCHED_CACHE;
+    int* const toff_l = cached ? cache_l + 2 * SCHED_CACHE : cache_l;
     const int t = threadIdx.x;
     if (t == 0) longest = 0;
     __syncthreads();
@@ -90,7 +104,7 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int T, SchedJob job0, SchedJ
         int ex = block_exclusive_scan(n, scan_buf, &total);
         if (s < B) {
             tile_off[s] = carry + ex;
-            if (cached) toff_l[s] = carry + ex;
+            if (cached || cached_offsets) toff_l[s] = carry + ex;
         }
         carry += total;
     }
@@ -114,6 +128,13 @@ sched_kernel(const int32_t* __restrict__ cu, int B, int T, SchedJob job0, SchedJ
                 if (toff_l[mid] <= idx) lo = mid; else hi = mid;
             }
             begin = beg_l[lo]; end = end_l[lo]; tile = idx - toff_l[lo];
+        } else if (cached_offsets) {
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (toff_l[mid] <= idx) lo = mid; else hi = mid;
+            }
+            sched_sample_rows(cu[lo], cu[lo + 1], T, begin, end);
+            tile = idx - toff_l[lo];
         } else {
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;

@@ -55,6 +55,8 @@ def _lengths_cases():
     yield "empty samples between", np.array([0, 300, 0, 0, 129, 1, 0, 128, 127, 0])
     yield "3000 samples (several passes of the 1024-thread scan)", rng.integers(0, 200, size=3000)
     yield "one sample", np.array([5000])
+    yield "9000 samples (tile offsets in LDS, sample bounds from cu_seqlens)", rng.integers(0, 150, size=9000)
+    yield "25000 samples (searches through the workspace)", rng.integers(0, 60, size=25000)
 
 
 @pytest.mark.parametrize("causal", [False, True])
