@@ -75,8 +75,8 @@ def test_equal_counts(method):
 def test_equal_counts_differencing_worked_examples():
     # By hand, 2 bins, cost = length.  {10,9,7,6,4,2}: the start is one partial solution per group of 2
     # consecutive values of the sorted order: A = (10|9), B = (7|6), C = (4|2), spreads 1, 1, 2.
-    # Round 1 merges the two of largest spread, C (2) and the earlier of the 1s, A, largest slot with
-    # smallest: (4+9 | 2+10) = (13|12).  Round 2 merges B and that: (7+12 | 6+13) = (19|19), and the
+    # The first merge step merges the two of largest spread, C (2) and the earlier of the 1s, A, largest slot with
+    # smallest: (4+9 | 2+10) = (13|12).  The second merges B and that: (7+12 | 6+13) = (19|19), and the
     # stable sort keeps the order: bin 0 = {7,2,10}, bin 1 = {6,4,9}.
     assert P.karmarkar_karp([10, 9, 7, 6, 4, 2], 2, lin=1.0, quad=0.0, equal_counts=True) == [0, 1, 0, 1, 1, 0]
     # {10,1,1,1}: A = (10|1) from indices 0, 1 and B = (1|1) from indices 2, 3 merge to
