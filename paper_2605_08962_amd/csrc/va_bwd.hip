@@ -914,8 +914,8 @@ template <int D, bool CAUSAL, bool MASKED>
 __device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const unsigned char* vt,
                                               const int (&aaddr)[BwdCfg<D>::KS], const int (&taddr)[BwdCfg<D>::DB][2],
                                               const bf16x8 (&qf)[BwdCfg<D>::KS], const bf16x8 (&dof)[BwdCfg<D>::KS],
-                                              f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2, float ndelta,
-                                              int kv0, int qrow, int L, int hh, bool lo) {
+                                              f32x16 (&dqacc)[BwdCfg<D>::DB], float c2, float lse2,
+                                              const f32x16& ndelta16, int kv0, int qrow, int L, int hh, bool lo) {
     using C = BwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
 #pragma unroll
@@ -923,13 +923,14 @@ __device__ __forceinline__ void dq_plain_step(const unsigned char* kt, const uns
         if (b) __builtin_amdgcn_sched_barrier(0);  // keep the second block's operand reads behind the first block
         f32x16 s, dp;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = ndelta; }
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
             bf16x8 ak = *(const bf16x8*)(kt + aaddr[ks] + b * 32 * ROWB);
             s = mfma32(ak, qf[ks], s);
             bf16x8 av = *(const bf16x8*)(vt + aaddr[ks] + b * 32 * ROWB);
-            dp = mfma32(av, dof[ks], dp);
+            // -Delta is where the dP accumulation starts: a 16-register constant read as the first MFMA's addend
+            dp = mfma32(av, dof[ks], ks == 0 ? ndelta16 : dp);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -1071,24 +1072,37 @@ dq_kernel_direct(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, con
     // causal: only a sample's first rows hold few terms.  Without the mask every masked step (the one holding the
     // sample's end) carries lo parts; the flag is hidden from the compiler all the same, so that the lo pass stays
     // behind a branch of its own: folded into the step it costs the kernel 10 registers it does not have.
+    f32x16 ndelta16;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ndelta16[r] = ndelta;
+    asm volatile("" : "+v"(ndelta16));  // one set of registers for the whole kernel, not a refill per block
     int always = 1;
     asm volatile("" : "+s"(always));
     const bool lo_steps = CAUSAL ? q0 == 0 : always != 0;
 
     // Step j: its loads (issued during step j - 1) have landed; the barrier publishes them and tells that every
     // wave is done with step j - 1, whose stage the loads of step j + 1 may now overwrite.
-    auto step = [&](int j, auto masked_tag) {
+    // PARITY: j % 2 where the caller knows it (-1 otherwise).  The mask-free loop runs two steps per iteration with
+    // the stage a constant in each, so that the LDS addresses of the operand reads are the per-lane offsets plus an
+    // immediate instead of one vector addition per address and step.
+    auto step = [&](int j, auto masked_tag, auto parity_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr int PARITY = decltype(parity_tag)::value;
         wait_vmcnt<0>();
         wg_barrier();
         issue_step(j + 1);
-        const unsigned char* st = lds + (j & 1) * STAGE;
-        dq_plain_step<D, CAUSAL, MASKED>(st, st + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta,
+        const unsigned char* st = lds + (PARITY >= 0 ? PARITY : (j & 1)) * STAGE;
+        dq_plain_step<D, CAUSAL, MASKED>(st, st + C::TILE, aaddr, taddr, qf, dof, dqacc, c2, lse2, ndelta16,
                                          j * BWD_STEP_KV, qrow, L, hh, lo_steps);
     };
+    using Unknown = std::integral_constant<int, -1>;
     int j = 0;
-    for (; j < n_plain; ++j) step(j, std::false_type{});
-    for (; j < nsteps; ++j) step(j, std::true_type{});
+    for (; j + 1 < n_plain; j += 2) {
+        step(j, std::false_type{}, std::integral_constant<int, 0>{});
+        step(j + 1, std::false_type{}, std::integral_constant<int, 1>{});
+    }
+    for (; j < n_plain; ++j) step(j, std::false_type{}, Unknown{});
+    for (; j < nsteps; ++j) step(j, std::true_type{}, Unknown{});
     wait_vmcnt<0>();
 
     if (qvalid) {
