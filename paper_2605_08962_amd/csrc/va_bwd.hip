@@ -461,10 +461,14 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
     f32x16 s, dpa, dpb;  // dP accumulators of the even / odd half, preloaded with -Delta
     float lv[16];
     bf16x8 pb[2], dsb[2];
-    auto phased = [&]() {
+    // STAGE_TAG: the step's stage where the caller knows it (-1 otherwise); with it the LDS addresses of the
+    // operand reads are per-lane offsets plus immediates instead of vector additions per step
+    auto phased = [&](auto stage_tag) {
+        constexpr int KNOWN = decltype(stage_tag)::value;
         VA_DKDV_SYNC()
-        const unsigned char* cur = lds + stage_i * STAGE;
-        const unsigned char* nxt = lds + (stage_i == NST - 1 ? 0 : stage_i + 1) * STAGE;
+        const int si = KNOWN >= 0 ? KNOWN : stage_i;
+        const unsigned char* cur = lds + si * STAGE;
+        const unsigned char* nxt = lds + (si == NST - 1 ? 0 : si + 1) * STAGE;
         // half 0 (the scalar bookkeeping of this step's loads runs behind its MFMAs)
         dkdv_load_lse<D, 0>(cur, lv, hh);
         dkdv_run_S<D>(fa, kf, s);
@@ -506,7 +510,17 @@ dkdv_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K, const __
         for (; st < n_head; ++st) VA_DKDV_CAREFUL(st)
         if (st < n_tail) {
             dkdv_load_A<D, 0>(lds + stage_i * STAGE, aaddr, fa, dpa, hh);
-            for (; st < n_tail; ++st) phased();
+            using Unknown = std::integral_constant<int, -1>;
+            if constexpr (D == 64) {  // (elsewhere the four copies of the step cost registers the kernel does not have)
+                for (; st < n_tail && stage_i != 0; ++st) phased(Unknown{});
+                for (; st + NST <= n_tail; st += NST) {  // whole rounds of the stages, each stage a constant
+                    phased(std::integral_constant<int, 0>{});
+                    phased(std::integral_constant<int, 1>{});
+                    phased(std::integral_constant<int, 2>{});
+                    phased(std::integral_constant<int, 3>{});
+                }
+            }
+            for (; st < n_tail; ++st) phased(Unknown{});
         }
         for (; st < nsteps; ++st) VA_DKDV_CAREFUL(st)
     }
