@@ -271,9 +271,13 @@ __device__ __forceinline__ int uniform_wave_id() { return __builtin_amdgcn_readf
 template <int D, int ROWS, bool MASK_BY_BRANCH = false>
 struct TileDma {
     using T = LdsTile<D>;
-    static_assert(ROWS == 64, "one block of 16 rows per wave");
-    static constexpr int NI = (T::BLOCK_POS + 63) / 64;  // load instructions per wave per tile
-    static constexpr int WAVE_BYTES = 16 * T::ROWB;      // LDS bytes of one wave's 16-row block
+    // 64-row tiles: one block of 16 rows per wave.  32-row tiles (head_dim 128 forward): 8 rows per wave, for the
+    // layouts whose rows hold data in every slot.
+    static_assert(ROWS == 64 || (ROWS == 32 && (D == 64 || D == 128)), "tile shape");
+    static constexpr int RPW = ROWS / 4;                                            // rows per wave
+    static constexpr int WAVE_POS = ROWS == 64 ? T::BLOCK_POS : RPW * (T::ROWB / 16);  // 16-byte positions per wave
+    static constexpr int NI = (WAVE_POS + 63) / 64;      // load instructions per wave per tile
+    static constexpr int WAVE_BYTES = RPW * T::ROWB;     // LDS bytes of one wave's rows
     uint32_t full[NI], last[NI];
     // lanes of load instruction i that hold data (a compile-time constant of the layout)
     __device__ __forceinline__ static constexpr uint64_t lane_mask(int i) {
@@ -281,7 +285,7 @@ struct TileDma {
         for (int lane = 0; lane < 64; ++lane) {
             const int p = 64 * i + lane;
             int r = 0, c = 0;
-            if (p < T::BLOCK_POS && T::locate(p, r, c)) m |= 1ull << lane;
+            if (ROWS == 32 ? p < WAVE_POS : (p < T::BLOCK_POS && T::locate(p, r, c))) m |= 1ull << lane;
         }
         return m;
     }
@@ -306,8 +310,14 @@ struct TileDma {
         for (int i = 0; i < NI; ++i) {
             const int p = 64 * i + lane;  // position inside this wave's block
             int r = 0, c = 0;
-            T::locate(p < T::BLOCK_POS ? p : 0, r, c);  // (a lane without data gets some valid offset; it never loads)
-            const int row = 16 * wave + r;
+            if constexpr (ROWS == 64) {
+                T::locate(p < T::BLOCK_POS ? p : 0, r, c);  // (a lane without data gets some valid offset; it never loads)
+            } else {  // 8 rows per wave: the swizzle goes by the row inside the tile
+                constexpr int SLOTS = T::ROWB / 16;
+                r = (p < WAVE_POS ? p : 0) / SLOTS;
+                c = ((p < WAVE_POS ? p : 0) % SLOTS) ^ T::swz(RPW * wave + r);
+            }
+            const int row = RPW * wave + r;
             full[i] = (uint32_t)row * row_bytes + c * 16;
             last[i] = (uint32_t)min(row, L - 1 - last_r0) * row_bytes + c * 16;
         }

@@ -19,7 +19,10 @@ namespace va {
 template <int D>
 struct FwdCfg {
     using T = LdsTile<D>;
-    static constexpr int BQ = FWD_TILE_Q, BKV = FWD_TILE_KV;
+    // Key tiles of 64 rows; 32 at head_dim 128, where the smaller tiles (and the 16 score registers they save)
+    // are what lets three workgroups share a CU instead of two.
+    static constexpr int BQ = FWD_TILE_Q, BKV = D == 128 ? 32 : FWD_TILE_KV;
+    static constexpr int NB = BKV / 32;                // 32-key blocks of S^T per tile
     static constexpr int KS = D / 16;                  // 16-deep steps of QK^T
     static constexpr int DB = (D + 31) / 32;           // 32-wide blocks of O^T rows
     static constexpr int TILE = BKV * T::ROWB;         // bytes of one K or V tile in LDS
@@ -50,9 +53,10 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
                                           float c2, int kv0, int L, int qrow, int hh, Issue& issue) {
     using C = FwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
-    f32x16 s[2];
+    constexpr int NB = C::NB;
+    f32x16 s[NB];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < NB; ++b) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
 #pragma unroll
@@ -62,9 +66,10 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         }
         if (FIRST_SLOT <= b) issue(b);
     }
-    bool ok[2][16];
+    if (NB == 1 && FIRST_SLOT <= 1) issue(1);
+    bool ok[NB][16];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int kv = kv0 + 32 * b + 8 * (r / 4) + 4 * hh + (r % 4);
@@ -73,7 +78,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         }
     float mx = s[0][0];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
     mx = xhalf_max(mx);
@@ -104,7 +109,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
     const float mc = m * c2;
     float rs = 0.f;
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float p = fast_exp2(__builtin_fmaf(s[b][r], c2, -mc));
@@ -114,9 +119,9 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
         }
     lsum += rs;
 
-    bf16x8 pb[2][2], plo[2][2];
+    bf16x8 pb[NB][2], plo[NB][2];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             pb[b][st] = pack8(s[b][8 * st + 0], s[b][8 * st + 1], s[b][8 * st + 2], s[b][8 * st + 3],
@@ -129,7 +134,7 @@ __device__ __forceinline__ void tile_step(const unsigned char* kb, const unsigne
 #pragma unroll
     for (int db = 0; db < C::DB; ++db) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
                 const unsigned char* p0 = vb + (32 * b + 16 * st) * ROWB;
@@ -159,9 +164,10 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
                                                    Issue& issue) {
     using C = FwdCfg<D>;
     constexpr int ROWB = C::T::ROWB;
-    f32x16 s[2];
+    constexpr int NB = C::NB;
+    f32x16 s[NB];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < NB; ++b) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
 #pragma unroll
@@ -171,10 +177,11 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
         }
         issue(b);
     }
+    if (NB == 1) issue(1);
     const float mc = m * c2;
     float rs = 0.f;
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             s[b][r] = fast_exp2(__builtin_fmaf(s[b][r], c2, -mc));
@@ -186,7 +193,7 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
 #pragma unroll
     for (int db = 0; db < C::DB; ++db) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
                 const bf16x8 pb = pack8(s[b][8 * st + 0], s[b][8 * st + 1], s[b][8 * st + 2], s[b][8 * st + 3],
@@ -205,9 +212,9 @@ __device__ __forceinline__ bool tile_step_trusting(const unsigned char* kb, cons
 // 8192-token samples, to two 18 %.  The lean form is compiled for three: under the causal mask it takes 149 registers
 // and spills at 128.
 template <int D, bool CAUSAL>
-constexpr int kFwdWgsPerCu = D == 64 ? 4 : D <= 80 ? 3 : 2;
+constexpr int kFwdWgsPerCu = D == 64 ? 4 : (D <= 80 || D == 128) ? 3 : 2;
 template <int D>
-constexpr int kFwdLeanWgsPerCu = D <= 80 ? 3 : 2;
+constexpr int kFwdLeanWgsPerCu = (D <= 80 || D == 128) ? 3 : 2;
 
 // One work item: the query tile `wid` names (see xcd_item_head), all its key tiles.  `lds` is the workgroup's
 // staging memory, 5 tiles (K x3, then V x2).
@@ -261,7 +268,12 @@ __device__ __forceinline__ void fwd_work_item(unsigned wid, unsigned char* lds, 
     const int ntiles = (kv_end + C::BKV - 1) / C::BKV;
     // tiles [0, n_plain) need no mask in any wave: whole tiles below the sample end and, under the
     // causal mask, entirely at or below the tile's first query row
-    const int n_plain = CAUSAL ? min(L, q0 + 1) / C::BKV : L / C::BKV;
+    // (rows that meet fewer than 64 keys before any mask do so in the first 64 / BKV tiles, which then all count
+    // as masked tiles and carry P as hi + lo, whatever the tile size)
+    const int keys_unmasked = CAUSAL ? min(L, q0 + 1) : L;
+    const bool few_keys = keys_unmasked < 64;
+    const int n_plain = few_keys ? 0 : keys_unmasked / C::BKV;
+    const int n_lo = few_keys ? 64 / C::BKV : 0;
     const int jb = S > 1 ? ntiles * ch / S : 0, je = S > 1 ? ntiles * (ch + 1) / S : ntiles;  // this chunk's tiles
     if (jb >= je) {  // fewer tiles than chunks: an empty part (its O is never read)
         if (qvalid && hh == 0) part_lse[((size_t)ch * Hq + h) * T + sb + qrow] = -INFINITY;
@@ -358,11 +370,20 @@ __device__ __forceinline__ void fwd_work_item(unsigned wid, unsigned char* lds, 
         kslot = kslot == 2 ? 0 : kslot + 1;                                                    \
         vslot ^= 1;
 
-    if (n_plain == 0 && j == 0) {  // a sample's first key tile with a mask: rows with very few keys (hi + lo P)
-        VA_FWD_ITER_BEGIN()
-        tile_step<D, CAUSAL, true, 0, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
-        VA_FWD_ITER_END()
-        ++j;
+    // a sample's first keys behind a mask: rows with very few keys (hi + lo P)
+    if constexpr (C::BKV == 64) {
+        if (few_keys && j == 0) {
+            VA_FWD_ITER_BEGIN()
+            tile_step<D, CAUSAL, true, 0, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+            VA_FWD_ITER_END()
+            ++j;
+        }
+    } else {
+        for (; j < min(n_lo, je); ++j) {
+            VA_FWD_ITER_BEGIN()
+            tile_step<D, CAUSAL, true, 0, true>(kb, vb, kaddr, vaddr, qf, oacc, m, lsum, c2, kv0, L, qrow, hh, issue);
+            VA_FWD_ITER_END()
+        }
     }
     if (j < min(n_plain, je)) {  // the first mask-free tile sets the reference maximum
         VA_FWD_ITER_BEGIN()
