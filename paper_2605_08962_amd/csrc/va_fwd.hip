@@ -7,7 +7,7 @@
 // per-lane scalars, and P^T (cast to bf16) already is the B operand of O^T = V^T P^T.  V^T is
 // read from a row-major LDS tile with the transposing LDS read.
 //
-// Staging.  K and V tiles of 64 rows go from HBM/L2 straight into LDS (direct-to-LDS loads, no
+// Staging.  K and V tiles of 64 rows (32 at head_dim 128) go from HBM/L2 straight into LDS (direct-to-LDS loads, no
 // registers in between).  K is triple-buffered and V double-buffered: while tile j is computed,
 // V(j+1) and K(j+2) are in flight, which covers the L2/HBM latency that a one-tile-ahead register
 // prefetch was measured to expose (about a third of the kernel time).
@@ -34,9 +34,9 @@ struct FwdCfg {
 // the first tiles of a sample that almost never happens, which saves the rescale multiplies.
 constexpr float kRescaleLog2 = 8.0f;
 
-// One 64-key tile for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// One key tile (FwdCfg<D>::BKV rows) for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
 // BOUNDARY tiles apply the sample-end / causal mask.  LO tiles also carry P as bf16 hi + lo: a
-// sample's first key tile, when it is a boundary tile, is where rows with only a handful of keys live
+// sample's first 64 keys, when a mask falls into them, are where rows with only a handful of keys live
 // (samples shorter than a tile, the first rows under the causal mask); their outputs are O(1), so a
 // single bf16 rounding of P would eat most of the 1e-2 tolerance.  A row that reaches any other
 // boundary tile sees at least 64 keys, and the rounding errors of its P average out.
